@@ -1,0 +1,155 @@
+"""ctypes binding of libgbmuf.so: argument marshalling only, same names as include/gbmuf.h.
+
+Device buffers are passed as integers (``tensor.data_ptr()``) or as any object with a
+``data_ptr()`` method; streams as ``torch.cuda.Stream.cuda_stream`` integers (0/None = the
+default stream).  Nothing here computes: every step runs in the library's kernels.  If the
+library has not been built the import of this module fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch  # noqa: F401  -- first: libgbmuf must bind to the HIP runtime that torch has loaded, not a second copy
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgbmuf.so")
+
+GBMUF_OK, GBMUF_EINVAL, GBMUF_ENOMEM, GBMUF_EDEVICE, GBMUF_EUNSUPPORTED = 0, 1, 2, 3, 4
+MODE_NO_RESTART, MODE_PAPER, MODE_LITERAL, MODE_GOSSIP_MA = 0, 1, 2, 3
+MAX_K = 1024
+
+
+class GbmufError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        detail = _lib.gbmuf_last_error_detail().decode()
+        super().__init__(f"{what}: {strerror(code)} (status {code})" + (f" [{detail}]" if detail else ""))
+
+
+class Info(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_int32), ("K", ctypes.c_int32), ("q", ctypes.c_int32), ("p", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("has_device", ctypes.c_int32), ("P", ctypes.c_int64),
+                ("n_tiles", ctypes.c_int64), ("tile_columns", ctypes.c_int32), ("threads", ctypes.c_int32),
+                ("seed", ctypes.c_uint64)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+            "or python -m paper_1909_09010_amd.build).  There is no fallback path.")
+    L = ctypes.CDLL(LIB_PATH)
+    i32, i64, u64, f32, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_float, ctypes.c_void_p
+    L.gbmuf_plan.argtypes = [ctypes.POINTER(vp), vp, i32, i32, i32, i32, u64]
+    L.gbmuf_plan_destroy.argtypes = [vp]
+    L.gbmuf_plan_info.argtypes = [vp, ctypes.POINTER(Info)]
+    L.gbmuf_candidates_host.argtypes = [vp, i32, vp]
+    L.gbmuf_neighbours_host.argtypes = [vp, u64, vp]
+    L.gbmuf_neighbours_device.argtypes = [vp, u64, vp, vp]
+    L.gbmuf_sync.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, u64, vp]
+    L.gbmuf_sync_table.argtypes = [vp, vp, vp, vp, vp, i64, f32, f32, i32, vp]
+    L.gbmuf_strerror.argtypes = [ctypes.c_int]
+    L.gbmuf_strerror.restype = ctypes.c_char_p
+    L.gbmuf_last_error_detail.argtypes = []
+    L.gbmuf_last_error_detail.restype = ctypes.c_char_p
+    for name in ("gbmuf_plan", "gbmuf_plan_destroy", "gbmuf_plan_info", "gbmuf_candidates_host",
+                 "gbmuf_neighbours_host", "gbmuf_neighbours_device", "gbmuf_sync", "gbmuf_sync_table"):
+        getattr(L, name).restype = ctypes.c_int
+    return L
+
+
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return _lib.gbmuf_strerror(code).decode()
+
+
+def _dev(x) -> Optional[int]:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    return int(x)
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    if hasattr(s, "cuda_stream"):
+        return int(s.cuda_stream) or None
+    return int(s) or None
+
+
+class Plan:
+    """Owns one ``gbmuf_plan_t``.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, comp_offsets: Sequence[int], K: int, q: int, p: int = 0, seed: int = 0):
+        off = np.ascontiguousarray(comp_offsets, dtype=np.int64)
+        if off.ndim != 1 or off.size < 1:
+            raise GbmufError(GBMUF_EINVAL, "gbmuf_plan")
+        self._h = ctypes.c_void_p()
+        rc = _lib.gbmuf_plan(ctypes.byref(self._h), off.ctypes.data_as(ctypes.c_void_p), off.size - 1, K, q, p,
+                             seed & 0xFFFFFFFFFFFFFFFF)
+        if rc != GBMUF_OK:
+            self._h = ctypes.c_void_p()
+            raise GbmufError(rc, "gbmuf_plan")
+        self.info = self.plan_info()
+
+    def destroy(self) -> None:
+        if getattr(self, "_h", None) is not None and self._h:
+            _lib.gbmuf_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def plan_info(self) -> Info:
+        info = Info()
+        rc = _lib.gbmuf_plan_info(self._h, ctypes.byref(info))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_plan_info")
+        return info
+
+    def candidates_host(self, w: int) -> np.ndarray:
+        out = np.zeros(max(self.info.C, 1), dtype=np.int32)
+        rc = _lib.gbmuf_candidates_host(self._h, w, out.ctypes.data_as(ctypes.c_void_p))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_candidates_host")
+        return out[: self.info.C].copy()
+
+    def neighbours_host(self, round: int) -> np.ndarray:
+        out = np.zeros((self.info.m, self.info.K, self.info.q), dtype=np.int32)
+        rc = _lib.gbmuf_neighbours_host(self._h, round, out.ctypes.data_as(ctypes.c_void_p))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_neighbours_host")
+        return out
+
+    def neighbours_device(self, round: int, out_dev, stream=None) -> None:
+        rc = _lib.gbmuf_neighbours_device(self._h, round, _dev(out_dev), _stream(stream))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_neighbours_device")
+
+    def sync(self, replicas, global_, delta, worker_stride: int, eta: float, zeta: float,
+             nesterov: int = MODE_PAPER, round: int = 0, stream=None) -> None:
+        rc = _lib.gbmuf_sync(self._h, _dev(replicas), _dev(global_), _dev(delta), worker_stride, eta, zeta,
+                             nesterov, round, _stream(stream))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_sync")
+
+    def sync_table(self, nbr_dev, replicas, global_, delta, worker_stride: int, eta: float, zeta: float,
+                   nesterov: int = MODE_PAPER, stream=None) -> None:
+        rc = _lib.gbmuf_sync_table(self._h, _dev(nbr_dev), _dev(replicas), _dev(global_), _dev(delta),
+                                   worker_stride, eta, zeta, nesterov, _stream(stream))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_sync_table")

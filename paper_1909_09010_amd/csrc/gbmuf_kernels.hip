@@ -1,0 +1,371 @@
+// gbmuf_kernels.hip -- gfx950 kernels of libgbmuf: the neighbour sampler and the fused
+// gather-average-momentum kernel (Algorithm 1, sync branch, of arXiv 1909.09010).
+//
+// Fused kernel, in one sentence: a workgroup owns a tile of T 16-byte columns of one
+// component for ALL K workers, parks the K x T block of theta in LDS (so every worker's
+// average reads its neighbours from LDS, and all reads of theta happen before any write:
+// the in-place update keeps snapshot semantics), and streams omega and Delta through
+// registers; every state byte is read once and written once.
+#include "gbmuf_internal.h"
+
+#include "../../include/gbmuf.h"
+
+// Every multiply and add below is rounded on its own: the reference arithmetic has no
+// fused multiply-add.  (The build also passes -ffp-contract=off.)
+#pragma clang fp contract(off)
+
+namespace gbmuf {
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// Neighbour sampler: one thread per (component, worker); the thread's copy of the
+// candidate list lives in LDS, interleaved so that thread t owns words t, t+TB, t+2TB...
+// ---------------------------------------------------------------------------------------
+struct LdsPerm {
+    int32_t *base;
+    int stride;
+    __device__ int32_t &operator()(int32_t x) const { return base[x * stride]; }
+};
+
+__global__ void sample_kernel(SampleArgs a)
+{
+    extern __shared__ int32_t perm_lds[];
+    const int tb = blockDim.x;
+    const int64_t pair = static_cast<int64_t>(blockIdx.x) * tb + threadIdx.x;
+    if (pair >= a.pairs) return;                      // no barrier below
+    const uint32_t comp = static_cast<uint32_t>(pair / a.K);
+    const uint32_t w = static_cast<uint32_t>(pair % a.K);
+    LdsPerm perm{perm_lds + threadIdx.x, tb};
+    const int32_t *cand = a.cand + static_cast<int64_t>(w) * a.C;
+    for (int32_t x = 0; x < a.C; ++x) perm(x) = cand[x];
+    draw_neighbours(perm, a.C, a.q, a.key0, a.key1, a.round0, a.round1, comp, w);
+    int32_t *row = a.out + pair * a.q;
+    for (int32_t j = 0; j < a.q; ++j) row[j] = perm(j);
+}
+
+// ---------------------------------------------------------------------------------------
+// The block-momentum filter and the restart for one element (Algorithm 1, gossip-BMUF
+// statements): G = avg - theta_{t-H};  Delta' = eta*Delta + zeta*G;  omega' = omega +
+// Delta';  theta' = omega' + eta*Delta'.  theta_{t-H} is omega + eta*Delta in the paper's
+// mode (what the previous restart wrote), omega otherwise.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ void filter(float avg, float om, float de, float eta, float zeta, int mode,
+                                       float &th_out, float &om_out, float &de_out)
+{
+    const float t = eta * de;
+    const float start = (mode == GBMUF_MODE_PAPER) ? om + t : om;
+    const float G = avg - start;
+    const float zg = zeta * G;
+    const float dn = t + zg;
+    const float on = om + dn;
+    float tn = on;
+    if (mode != GBMUF_MODE_NO_RESTART) {
+        const float r = eta * dn;
+        tn = on + r;
+    }
+    th_out = tn; om_out = on; de_out = dn;
+}
+
+// Neighbour rows of this tile's component -> LDS, merged with the worker itself and sorted
+// ascending: ids[w][0..q].  Ids are clamped into [0, K) so that a bad caller table cannot
+// index outside the tile.
+__device__ __forceinline__ void stage_ids(uint16_t *ids, const int32_t *nbr, int comp, int K, int q,
+                                          int tid, int nthreads)
+{
+    for (int w = tid; w < K; w += nthreads) {
+        const int32_t *row = nbr + (static_cast<int64_t>(comp) * K + w) * q;
+        uint16_t *dst = ids + w * (q + 1);
+        dst[0] = static_cast<uint16_t>(w);
+        for (int j = 0; j < q; ++j) {
+            int v = row[j];
+            v = v < 0 ? 0 : (v >= K ? K - 1 : v);
+            int b = j;
+            while (b >= 0 && dst[b] > v) { dst[b + 1] = dst[b]; --b; }
+            dst[b + 1] = static_cast<uint16_t>(v);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// 16-byte path: worker rows are 16-byte aligned (bases and stride), a column is 4 floats.
+// Q1 = q+1 when known at compile time (the sum is then fully unrolled), 0 = run-time q.
+// Slot s of the tile (s = tid + n*NT) is worker s >> logT, column s & (T-1).
+// ---------------------------------------------------------------------------------------
+template <int NT, int SLOTS, int Q1>
+__global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
+{
+    extern __shared__ float4 lds4[];
+    float4 *tile = lds4;
+    uint16_t *ids = reinterpret_cast<uint16_t *>(lds4 + NT * SLOTS);
+
+    const int tid = threadIdx.x;
+    const TileDesc td = a.tiles[blockIdx.x];
+    const int K = a.K, q = a.q, q1 = (Q1 > 0) ? Q1 : a.q + 1;
+    const int logT = a.logT, T = 1 << logT;
+    const int mode = a.mode;
+    const int64_t lo = td.lo, hi = td.lo + td.n;
+    const int64_t g0 = lo >> 2;                                  // first 4-float column
+    const int ncols = static_cast<int>(((hi + 3) >> 2) - g0);     // <= T
+
+    float4 th[SLOTS], om[SLOTS], de[SLOTS];
+    unsigned mask[SLOTS];                                         // which of the 4 floats are ours
+
+#pragma unroll
+    for (int n = 0; n < SLOTS; ++n) {
+        const int slot = tid + n * NT;
+        const int w = slot >> logT, col = slot & (T - 1);
+        unsigned mk = 0;
+        const int64_t e = (g0 + col) << 2;
+        if (w < K && col < ncols) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) mk |= (e + c >= lo && e + c < hi) ? (1u << c) : 0u;
+        }
+        mask[n] = mk;
+        th[n] = make_float4(0.f, 0.f, 0.f, 0.f);
+        om[n] = th[n];
+        de[n] = th[n];
+        const int64_t at = static_cast<int64_t>(w) * a.stride + e;
+        if (mk == 0xFu) {
+            th[n] = *reinterpret_cast<const float4 *>(a.theta + at);
+            if (mode != GBMUF_MODE_GOSSIP_MA) {
+                om[n] = *reinterpret_cast<const float4 *>(a.omega + at);
+                de[n] = *reinterpret_cast<const float4 *>(a.delta + at);
+            }
+        } else if (mk != 0u) {                                    // a column cut by a component edge
+            float *t4 = reinterpret_cast<float *>(&th[n]);
+            float *o4 = reinterpret_cast<float *>(&om[n]);
+            float *d4 = reinterpret_cast<float *>(&de[n]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (mk & (1u << c)) {
+                    t4[c] = a.theta[at + c];
+                    if (mode != GBMUF_MODE_GOSSIP_MA) { o4[c] = a.omega[at + c]; d4[c] = a.delta[at + c]; }
+                }
+            }
+        }
+    }
+
+    stage_ids(ids, a.nbr, td.comp, K, q, tid, NT);
+
+#pragma unroll
+    for (int n = 0; n < SLOTS; ++n) tile[tid + n * NT] = th[n];
+    __syncthreads();
+
+#pragma unroll
+    for (int n = 0; n < SLOTS; ++n) {
+        const unsigned mk = mask[n];
+        if (mk == 0u) continue;
+        const int slot = tid + n * NT;
+        const int w = slot >> logT, col = slot & (T - 1);
+        const uint16_t *row = ids + w * q1;
+
+        // sum over the worker and its neighbours, ascending worker id, then * 1/(q+1)
+        float4 s = tile[(static_cast<int>(row[0]) << logT) + col];
+        if (Q1 > 0) {
+#pragma unroll
+            for (int j = 1; j < Q1; ++j) {
+                const float4 v = tile[(static_cast<int>(row[j]) << logT) + col];
+                s.x = s.x + v.x; s.y = s.y + v.y; s.z = s.z + v.z; s.w = s.w + v.w;
+            }
+        } else {
+            for (int j = 1; j < q1; ++j) {
+                const float4 v = tile[(static_cast<int>(row[j]) << logT) + col];
+                s.x = s.x + v.x; s.y = s.y + v.y; s.z = s.z + v.z; s.w = s.w + v.w;
+            }
+        }
+        float4 tn, on, dn;
+        tn.x = s.x * a.inv; tn.y = s.y * a.inv; tn.z = s.z * a.inv; tn.w = s.w * a.inv;
+        if (mode != GBMUF_MODE_GOSSIP_MA) {
+            const float4 avg = tn;
+            filter(avg.x, om[n].x, de[n].x, a.eta, a.zeta, mode, tn.x, on.x, dn.x);
+            filter(avg.y, om[n].y, de[n].y, a.eta, a.zeta, mode, tn.y, on.y, dn.y);
+            filter(avg.z, om[n].z, de[n].z, a.eta, a.zeta, mode, tn.z, on.z, dn.z);
+            filter(avg.w, om[n].w, de[n].w, a.eta, a.zeta, mode, tn.w, on.w, dn.w);
+        }
+        const int64_t at = static_cast<int64_t>(w) * a.stride + ((g0 + col) << 2);
+        if (mk == 0xFu) {
+            *reinterpret_cast<float4 *>(a.theta + at) = tn;
+            if (mode != GBMUF_MODE_GOSSIP_MA) {
+                *reinterpret_cast<float4 *>(a.omega + at) = on;
+                *reinterpret_cast<float4 *>(a.delta + at) = dn;
+            }
+        } else {
+            const float *t4 = reinterpret_cast<const float *>(&tn);
+            const float *o4 = reinterpret_cast<const float *>(&on);
+            const float *d4 = reinterpret_cast<const float *>(&dn);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (mk & (1u << c)) {
+                    a.theta[at + c] = t4[c];
+                    if (mode != GBMUF_MODE_GOSSIP_MA) { a.omega[at + c] = o4[c]; a.delta[at + c] = d4[c]; }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// 4-byte path for rows that are not 16-byte aligned: the same tile is walked in passes of
+// T single-float columns.
+// ---------------------------------------------------------------------------------------
+template <int NT, int SLOTS>
+__global__ __launch_bounds__(NT) void sync_vec1_kernel(SyncArgs a)
+{
+    extern __shared__ float4 lds4[];
+    float *tile = reinterpret_cast<float *>(lds4);
+    uint16_t *ids = reinterpret_cast<uint16_t *>(tile + NT * SLOTS);
+
+    const int tid = threadIdx.x;
+    const TileDesc td = a.tiles[blockIdx.x];
+    const int K = a.K, q = a.q, q1 = a.q + 1;
+    const int logT = a.logT, T = 1 << logT;
+    const int mode = a.mode;
+    const int64_t hi = td.lo + td.n;
+
+    stage_ids(ids, a.nbr, td.comp, K, q, tid, NT);
+
+    for (int64_t first = td.lo; first < hi; first += T) {
+        const int ncols = static_cast<int>(hi - first < T ? hi - first : T);
+        float th[SLOTS], om[SLOTS], de[SLOTS];
+#pragma unroll
+        for (int n = 0; n < SLOTS; ++n) {
+            const int slot = tid + n * NT;
+            const int w = slot >> logT, col = slot & (T - 1);
+            th[n] = 0.f; om[n] = 0.f; de[n] = 0.f;
+            if (w < K && col < ncols) {
+                const int64_t at = static_cast<int64_t>(w) * a.stride + first + col;
+                th[n] = a.theta[at];
+                if (mode != GBMUF_MODE_GOSSIP_MA) { om[n] = a.omega[at]; de[n] = a.delta[at]; }
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < SLOTS; ++n) tile[tid + n * NT] = th[n];
+        __syncthreads();
+#pragma unroll
+        for (int n = 0; n < SLOTS; ++n) {
+            const int slot = tid + n * NT;
+            const int w = slot >> logT, col = slot & (T - 1);
+            if (!(w < K && col < ncols)) continue;
+            const uint16_t *row = ids + w * q1;
+            float s = tile[(static_cast<int>(row[0]) << logT) + col];
+            for (int j = 1; j < q1; ++j) s = s + tile[(static_cast<int>(row[j]) << logT) + col];
+            float tn = s * a.inv, on = 0.f, dn = 0.f;
+            const int64_t at = static_cast<int64_t>(w) * a.stride + first + col;
+            if (mode != GBMUF_MODE_GOSSIP_MA) {
+                const float avg = tn;
+                filter(avg, om[n], de[n], a.eta, a.zeta, mode, tn, on, dn);
+                a.omega[at] = on;
+                a.delta[at] = dn;
+            }
+            a.theta[at] = tn;
+        }
+        __syncthreads();                                          // tile is reused by the next pass
+    }
+}
+
+constexpr Variant kVariants[] = {
+    {256, 8}, {512, 8}, {512, 4}, {256, 16}, {1024, 4}, {256, 4},
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+using KernelFn = void (*)(SyncArgs);
+
+template <int NT, int SLOTS>
+KernelFn pick_vec4(int q1)
+{
+    switch (q1) {
+        case 1: return sync_vec4_kernel<NT, SLOTS, 1>;
+        case 2: return sync_vec4_kernel<NT, SLOTS, 2>;
+        case 3: return sync_vec4_kernel<NT, SLOTS, 3>;
+        case 4: return sync_vec4_kernel<NT, SLOTS, 4>;
+        case 5: return sync_vec4_kernel<NT, SLOTS, 5>;
+        default: return sync_vec4_kernel<NT, SLOTS, 0>;
+    }
+}
+
+KernelFn pick_kernel(const Variant &v, bool vec4, int q1)
+{
+#define GBMUF_CASE(NT, SL) \
+    if (v.threads == NT && v.slots == SL) return vec4 ? pick_vec4<NT, SL>(q1) : sync_vec1_kernel<NT, SL>;
+    GBMUF_CASE(256, 8)
+    GBMUF_CASE(512, 8)
+    GBMUF_CASE(512, 4)
+    GBMUF_CASE(256, 16)
+    GBMUF_CASE(1024, 4)
+    GBMUF_CASE(256, 4)
+#undef GBMUF_CASE
+    return nullptr;
+}
+
+size_t ids_bytes(int K, int q)
+{
+    return (static_cast<size_t>(K) * static_cast<size_t>(q + 1) * sizeof(uint16_t) + 15) & ~static_cast<size_t>(15);
+}
+
+}  // namespace
+
+const Variant *variant_table(int *count)
+{
+    *count = kNumVariants;
+    return kVariants;
+}
+
+// Raises the dynamic-LDS limit of the kernels this plan will launch and reports the LDS
+// bytes one workgroup uses (16-byte path).  GBMUF_EUNSUPPORTED if that exceeds the device.
+int prepare_kernels(const Variant &v, int K, int q, size_t *lds_bytes_out)
+{
+    const size_t lds4 = static_cast<size_t>(v.threads) * v.slots * sizeof(float4) + ids_bytes(K, q);
+    const size_t lds1 = static_cast<size_t>(v.threads) * v.slots * sizeof(float) + ids_bytes(K, q);
+    *lds_bytes_out = lds4;
+    int dev = 0, max_lds = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return hip_failed("hipGetDevice", err, GBMUF_EDEVICE);
+    err = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev);
+    if (err != hipSuccess) return hip_failed("hipDeviceGetAttribute(MaxSharedMemoryPerBlock)", err, GBMUF_EDEVICE);
+    if (lds4 > static_cast<size_t>(max_lds)) return GBMUF_EUNSUPPORTED;
+    KernelFn k4 = pick_kernel(v, true, q + 1), k1 = pick_kernel(v, false, q + 1);
+    if (!k4 || !k1) return GBMUF_EINVAL;
+    err = hipFuncSetAttribute(reinterpret_cast<const void *>(k4), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              static_cast<int>(lds4));
+    if (err != hipSuccess) return hip_failed("hipFuncSetAttribute(16-byte kernel)", err, GBMUF_EDEVICE);
+    err = hipFuncSetAttribute(reinterpret_cast<const void *>(k1), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              static_cast<int>(lds1));
+    if (err != hipSuccess) return hip_failed("hipFuncSetAttribute(4-byte kernel)", err, GBMUF_EDEVICE);
+    return GBMUF_OK;
+}
+
+int launch_sync(const Variant &v, bool vec4, const SyncArgs &a, int64_t n_tiles, hipStream_t stream)
+{
+    if (n_tiles <= 0) return GBMUF_OK;
+    if (n_tiles > 0x7fffffffLL) return GBMUF_EUNSUPPORTED;
+    KernelFn k = pick_kernel(v, vec4, a.q + 1);
+    if (!k) return GBMUF_EINVAL;
+    const size_t lds = static_cast<size_t>(v.threads) * v.slots * (vec4 ? sizeof(float4) : sizeof(float)) +
+                       ids_bytes(a.K, a.q);
+    SyncArgs args = a;
+    void *argv[] = {&args};
+    // the launch's own status: an earlier, unrelated error of the process is not ours to report
+    const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(k), dim3(static_cast<unsigned>(n_tiles)),
+                                           dim3(v.threads), argv, lds, stream);
+    return err == hipSuccess ? GBMUF_OK : hip_failed("hipLaunchKernel(sync)", err, GBMUF_EDEVICE);
+}
+
+int launch_sampler(const SampleArgs &a, hipStream_t stream)
+{
+    if (a.pairs <= 0 || a.q <= 0) return GBMUF_OK;
+    // each thread keeps C ints in LDS: as many threads as fit 48 KB, at most 64
+    int tb = 64;
+    while (tb > 1 && static_cast<size_t>(tb) * a.C * sizeof(int32_t) > 48 * 1024) tb >>= 1;
+    if (static_cast<size_t>(tb) * a.C * sizeof(int32_t) > 48 * 1024) return GBMUF_EUNSUPPORTED;
+    const int64_t blocks = (a.pairs + tb - 1) / tb;
+    if (blocks > 0x7fffffffLL) return GBMUF_EUNSUPPORTED;
+    SampleArgs args = a;
+    void *argv[] = {&args};
+    const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(sample_kernel),
+                                           dim3(static_cast<unsigned>(blocks)), dim3(tb), argv,
+                                           static_cast<size_t>(tb) * a.C * sizeof(int32_t), stream);
+    return err == hipSuccess ? GBMUF_OK : hip_failed("hipLaunchKernel(sampler)", err, GBMUF_EDEVICE);
+}
+
+}  // namespace gbmuf
