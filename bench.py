@@ -40,7 +40,7 @@ def measured_traffic(workload: str):
         return None
 
 
-def run_gpu(w, steps: int, warmup: int):
+def run_gpu(w, steps: int, warmup: int, contiguous: bool = False):
     import numpy as np
     import torch
 
@@ -51,12 +51,14 @@ def run_gpu(w, steps: int, warmup: int):
     P = int(off[-1])
     m = len(off) - 1
     t0 = time.perf_counter()
-    theta, omega, delta = workloads.init_state(w, dev)
-    stride = theta.shape[1]
+    span = None if contiguous else workloads.default_span_bytes(dev, 3 * w.K * workloads.padded_stride(P) * 4)
+    theta, omega, delta = workloads.init_state(w, dev, span_bytes=span)
+    stride = theta.stride(0)
     plan = binding.Plan(off, w.K, w.q, w.p, seed=w.seed)
     torch.cuda.synchronize()
     log(f"[bench] {w.name}: K={w.K} q={w.q} p={plan.info.p} P={P} m={m} tiles={plan.info.n_tiles} "
-        f"state={3 * w.K * stride * 4 / 1e9:.1f} GB, init {time.perf_counter() - t0:.1f}s")
+        f"state={3 * w.K * theta.shape[1] * 4 / 1e9:.1f} GB, row stride {stride * 4 / 1e9:.2f} GB, "
+        f"HBM span {(w.K - 1) * stride * 4 / 1e9 + 3 * theta.shape[1] * 4 / 1e9:.0f} GB, init {time.perf_counter() - t0:.1f}s")
     stream = torch.cuda.current_stream()
 
     rnd = 0
@@ -89,7 +91,8 @@ def run_gpu(w, steps: int, warmup: int):
     plan.destroy()
     del theta, omega, delta, nbr
     torch.cuda.empty_cache()
-    return dict(P=P, m=m, K=w.K, stride=stride, elapsed=elapsed, kernel_ms=kernel_ms, finite=finite)
+    return dict(P=P, m=m, K=w.K, stride=stride, padded=workloads.padded_stride(P), elapsed=elapsed,
+                kernel_ms=kernel_ms, finite=finite, layout="contiguous" if span is None else "interleaved_rows")
 
 
 def run_cpu_baseline(w, target_seconds: float = 15.0):
@@ -137,6 +140,8 @@ def main() -> int:
                     help="name or index into the benchmark configurations (default: configs[2], large_vocab)")
     ap.add_argument("--all", action="store_true", help="also time configs[1], [3], [4] and the 4-layer K=64 variant")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--contiguous", action="store_true",
+                    help="three separate contiguous [K, P] tensors instead of the HBM-spanning row layout")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (K workers are replicas in one GPU's HBM); "
@@ -152,7 +157,7 @@ def main() -> int:
         return 3
 
     w = workloads.get(args.workload)
-    g = run_gpu(w, args.steps, args.warmup)
+    g = run_gpu(w, args.steps, args.warmup, args.contiguous)
     wp = g["K"] * g["P"]
     value = wp * args.steps / g["elapsed"]
     algo_bytes = BYTES_PER_WORKER_PARAM * wp
@@ -172,7 +177,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "K": w.K, "q": w.q, "params_per_worker": g["P"], "components": g["m"],
                    "eta": w.eta, "zeta": w.zeta, "mode": "nesterov" if w.mode == 1 else str(w.mode),
-                   "state_GB": 3 * w.K * g["stride"] * 4 / 1e9},
+                   "state_GB": 3 * w.K * g["padded"] * 4 / 1e9, "layout": g["layout"],
+                   "row_stride_GB": g["stride"] * 4 / 1e9},
         "effective_GBps": BYTES_PER_WORKER_PARAM * value / 1e9,
         "pct_of_hbm_peak": 100.0 * BYTES_PER_WORKER_PARAM * value / 1e9 / HBM_PEAK_GBPS,
         "finite": g["finite"],
@@ -187,7 +193,7 @@ def main() -> int:
                 continue
             ww = workloads.get(name)
             steps = min(args.steps, ww.rounds)
-            gg = run_gpu(ww, steps, args.warmup)
+            gg = run_gpu(ww, steps, args.warmup, args.contiguous)
             v = gg["K"] * gg["P"] * steps / gg["elapsed"]
             kb = BYTES_PER_WORKER_PARAM * gg["K"] * gg["P"] / (gg["kernel_ms"] * 1e-3) / 1e9
             others.append({"workload": name, "value": v, "ms_per_step": gg["elapsed"] / steps * 1e3,

@@ -152,6 +152,16 @@ int gbmuf_sync_table(const gbmuf_plan_t *plan, const int32_t *nbr_dev, float *re
                      float *global, float *delta, int64_t worker_stride, float eta,
                      float zeta, int32_t nesterov, void *stream);
 
+/*
+ * Calibration probe, not part of the method: a plain streaming copy of n_floats floats
+ * (a multiple of 4; both pointers device memory, 16-byte aligned, not overlapping) with
+ * one read and one write per byte.  It gives hardware byte counters a launch of known
+ * traffic (4 * n_floats bytes read, 4 * n_floats written) and shows the bandwidth a 1:1 read/write
+ * stream reaches on the device.  flags: bit 0 = streaming stores, bit 1 = streaming loads.
+ */
+int gbmuf_probe_copy(float *dst_dev, const float *src_dev, int64_t n_floats, int32_t flags,
+                     void *stream);
+
 /* Static description of a status code. */
 const char *gbmuf_strerror(int code);
 

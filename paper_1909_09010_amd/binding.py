@@ -51,6 +51,8 @@ def _load() -> ctypes.CDLL:
     L.gbmuf_neighbours_device.argtypes = [vp, u64, vp, vp]
     L.gbmuf_sync.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, u64, vp]
     L.gbmuf_sync_table.argtypes = [vp, vp, vp, vp, vp, i64, f32, f32, i32, vp]
+    L.gbmuf_probe_copy.argtypes = [vp, vp, i64, i32, vp]
+    L.gbmuf_probe_copy.restype = ctypes.c_int
     L.gbmuf_strerror.argtypes = [ctypes.c_int]
     L.gbmuf_strerror.restype = ctypes.c_char_p
     L.gbmuf_last_error_detail.argtypes = []
@@ -86,6 +88,12 @@ def _stream(s) -> Optional[int]:
     if hasattr(s, "cuda_stream"):
         return int(s.cuda_stream) or None
     return int(s) or None
+
+
+def probe_copy(dst_dev, src_dev, n_floats: int, flags: int = 0, stream=None) -> None:
+    rc = _lib.gbmuf_probe_copy(_dev(dst_dev), _dev(src_dev), n_floats, flags, _stream(stream))
+    if rc != GBMUF_OK:
+        raise GbmufError(rc, "gbmuf_probe_copy")
 
 
 class Plan:

@@ -28,6 +28,7 @@ struct SyncArgs {
     int32_t logT;            // log2(columns per tile)
     int32_t mode;            // GBMUF_MODE_*
     float eta, zeta, inv;    // inv = 1/(q+1), rounded once on the host
+    int32_t flags;           // bit 0: streaming (nontemporal) stores, bit 1: streaming loads
 };
 
 // Arguments of the neighbour-sampling kernel.
@@ -107,6 +108,7 @@ int hip_failed(const char *what, hipError_t err, int status);
 
 // kernels.hip
 int launch_sampler(const SampleArgs &a, hipStream_t stream);
+int launch_copy_probe(float *dst, const float *src, int64_t n_floats, int flags, int blocks, hipStream_t stream);
 int launch_sync(const Variant &v, bool vec4, const SyncArgs &a, int64_t n_tiles, hipStream_t stream);
 int prepare_kernels(const Variant &v, int K, int q, size_t *lds_bytes_out);
 const Variant *variant_table(int *count);

@@ -92,11 +92,26 @@ __device__ __forceinline__ void stage_ids(uint16_t *ids, const int32_t *nbr, int
 // Q1 = q+1 when known at compile time (the sum is then fully unrolled), 0 = run-time q.
 // Slot s of the tile (s = tid + n*NT) is worker s >> logT, column s & (T-1).
 // ---------------------------------------------------------------------------------------
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4f load4(const float *p, bool streaming)
+{
+    const v4f *q = reinterpret_cast<const v4f *>(p);
+    return streaming ? __builtin_nontemporal_load(q) : *q;
+}
+
+__device__ __forceinline__ void store4(float *p, v4f v, bool streaming)
+{
+    v4f *q = reinterpret_cast<v4f *>(p);
+    if (streaming) __builtin_nontemporal_store(v, q);
+    else *q = v;
+}
+
 template <int NT, int SLOTS, int Q1>
 __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
 {
     extern __shared__ float4 lds4[];
-    float4 *tile = lds4;
+    v4f *tile = reinterpret_cast<v4f *>(lds4);
     uint16_t *ids = reinterpret_cast<uint16_t *>(lds4 + NT * SLOTS);
 
     const int tid = threadIdx.x;
@@ -104,11 +119,12 @@ __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
     const int K = a.K, q = a.q, q1 = (Q1 > 0) ? Q1 : a.q + 1;
     const int logT = a.logT, T = 1 << logT;
     const int mode = a.mode;
+    const bool nt_load = (a.flags & 2) != 0, nt_store = (a.flags & 1) != 0;
     const int64_t lo = td.lo, hi = td.lo + td.n;
     const int64_t g0 = lo >> 2;                                  // first 4-float column
     const int ncols = static_cast<int>(((hi + 3) >> 2) - g0);     // <= T
 
-    float4 th[SLOTS], om[SLOTS], de[SLOTS];
+    v4f th[SLOTS], om[SLOTS], de[SLOTS];
     unsigned mask[SLOTS];                                         // which of the 4 floats are ours
 
 #pragma unroll
@@ -122,25 +138,22 @@ __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
             for (int c = 0; c < 4; ++c) mk |= (e + c >= lo && e + c < hi) ? (1u << c) : 0u;
         }
         mask[n] = mk;
-        th[n] = make_float4(0.f, 0.f, 0.f, 0.f);
+        th[n] = v4f{0.f, 0.f, 0.f, 0.f};
         om[n] = th[n];
         de[n] = th[n];
         const int64_t at = static_cast<int64_t>(w) * a.stride + e;
         if (mk == 0xFu) {
-            th[n] = *reinterpret_cast<const float4 *>(a.theta + at);
+            th[n] = load4(a.theta + at, nt_load);
             if (mode != GBMUF_MODE_GOSSIP_MA) {
-                om[n] = *reinterpret_cast<const float4 *>(a.omega + at);
-                de[n] = *reinterpret_cast<const float4 *>(a.delta + at);
+                om[n] = load4(a.omega + at, nt_load);
+                de[n] = load4(a.delta + at, nt_load);
             }
         } else if (mk != 0u) {                                    // a column cut by a component edge
-            float *t4 = reinterpret_cast<float *>(&th[n]);
-            float *o4 = reinterpret_cast<float *>(&om[n]);
-            float *d4 = reinterpret_cast<float *>(&de[n]);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (mk & (1u << c)) {
-                    t4[c] = a.theta[at + c];
-                    if (mode != GBMUF_MODE_GOSSIP_MA) { o4[c] = a.omega[at + c]; d4[c] = a.delta[at + c]; }
+                    th[n][c] = a.theta[at + c];
+                    if (mode != GBMUF_MODE_GOSSIP_MA) { om[n][c] = a.omega[at + c]; de[n][c] = a.delta[at + c]; }
                 }
             }
         }
@@ -161,47 +174,51 @@ __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
         const uint16_t *row = ids + w * q1;
 
         // sum over the worker and its neighbours, ascending worker id, then * 1/(q+1)
-        float4 s = tile[(static_cast<int>(row[0]) << logT) + col];
+        v4f s = tile[(static_cast<int>(row[0]) << logT) + col];
         if (Q1 > 0) {
 #pragma unroll
-            for (int j = 1; j < Q1; ++j) {
-                const float4 v = tile[(static_cast<int>(row[j]) << logT) + col];
-                s.x = s.x + v.x; s.y = s.y + v.y; s.z = s.z + v.z; s.w = s.w + v.w;
-            }
+            for (int j = 1; j < Q1; ++j) s = s + tile[(static_cast<int>(row[j]) << logT) + col];
         } else {
-            for (int j = 1; j < q1; ++j) {
-                const float4 v = tile[(static_cast<int>(row[j]) << logT) + col];
-                s.x = s.x + v.x; s.y = s.y + v.y; s.z = s.z + v.z; s.w = s.w + v.w;
-            }
+            for (int j = 1; j < q1; ++j) s = s + tile[(static_cast<int>(row[j]) << logT) + col];
         }
-        float4 tn, on, dn;
-        tn.x = s.x * a.inv; tn.y = s.y * a.inv; tn.z = s.z * a.inv; tn.w = s.w * a.inv;
+        v4f tn = s * a.inv, on = tn, dn = tn;
         if (mode != GBMUF_MODE_GOSSIP_MA) {
-            const float4 avg = tn;
-            filter(avg.x, om[n].x, de[n].x, a.eta, a.zeta, mode, tn.x, on.x, dn.x);
-            filter(avg.y, om[n].y, de[n].y, a.eta, a.zeta, mode, tn.y, on.y, dn.y);
-            filter(avg.z, om[n].z, de[n].z, a.eta, a.zeta, mode, tn.z, on.z, dn.z);
-            filter(avg.w, om[n].w, de[n].w, a.eta, a.zeta, mode, tn.w, on.w, dn.w);
+            const v4f avg = tn;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                float t1, o1, d1;
+                filter(avg[c], om[n][c], de[n][c], a.eta, a.zeta, mode, t1, o1, d1);
+                tn[c] = t1; on[c] = o1; dn[c] = d1;
+            }
         }
         const int64_t at = static_cast<int64_t>(w) * a.stride + ((g0 + col) << 2);
         if (mk == 0xFu) {
-            *reinterpret_cast<float4 *>(a.theta + at) = tn;
+            store4(a.theta + at, tn, nt_store);
             if (mode != GBMUF_MODE_GOSSIP_MA) {
-                *reinterpret_cast<float4 *>(a.omega + at) = on;
-                *reinterpret_cast<float4 *>(a.delta + at) = dn;
+                store4(a.omega + at, on, nt_store);
+                store4(a.delta + at, dn, nt_store);
             }
         } else {
-            const float *t4 = reinterpret_cast<const float *>(&tn);
-            const float *o4 = reinterpret_cast<const float *>(&on);
-            const float *d4 = reinterpret_cast<const float *>(&dn);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (mk & (1u << c)) {
-                    a.theta[at + c] = t4[c];
-                    if (mode != GBMUF_MODE_GOSSIP_MA) { a.omega[at + c] = o4[c]; a.delta[at + c] = d4[c]; }
+                    a.theta[at + c] = tn[c];
+                    if (mode != GBMUF_MODE_GOSSIP_MA) { a.omega[at + c] = on[c]; a.delta[at + c] = dn[c]; }
                 }
             }
         }
+    }
+}
+
+// Plain streaming copy of n 16-byte words (calibration of HBM counters and a reference for
+// the bandwidth a 1:1 read/write stream reaches on this device).
+__global__ __launch_bounds__(256) void copy_probe_kernel(v4f *dst, const v4f *src, int64_t n, int flags)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const v4f v = (flags & 2) ? __builtin_nontemporal_load(src + i) : src[i];
+        if (flags & 1) __builtin_nontemporal_store(v, dst + i);
+        else dst[i] = v;
     }
 }
 
@@ -349,6 +366,18 @@ int launch_sync(const Variant &v, bool vec4, const SyncArgs &a, int64_t n_tiles,
     const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(k), dim3(static_cast<unsigned>(n_tiles)),
                                            dim3(v.threads), argv, lds, stream);
     return err == hipSuccess ? GBMUF_OK : hip_failed("hipLaunchKernel(sync)", err, GBMUF_EDEVICE);
+}
+
+int launch_copy_probe(float *dst, const float *src, int64_t n_floats, int flags, int blocks, hipStream_t stream)
+{
+    int64_t n = n_floats / 4;
+    if (n <= 0) return GBMUF_OK;
+    v4f *d = reinterpret_cast<v4f *>(dst);
+    const v4f *s = reinterpret_cast<const v4f *>(src);
+    void *argv[] = {&d, &s, &n, &flags};
+    const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(copy_probe_kernel), dim3(blocks), dim3(256),
+                                           argv, 0, stream);
+    return err == hipSuccess ? GBMUF_OK : hip_failed("hipLaunchKernel(copy probe)", err, GBMUF_EDEVICE);
 }
 
 int launch_sampler(const SampleArgs &a, hipStream_t stream)

@@ -22,6 +22,7 @@ struct gbmuf_plan_s {
     Variant variant{256, 8};
     int32_t logT = 0;
     float inv = 1.0f;                // 1/(q+1), rounded once
+    int32_t flags = 0;               // load/store cache hints of the fused kernel
 
     bool has_device = false;
     int device = -1;
@@ -159,6 +160,7 @@ int enqueue_sync(const gbmuf_plan_s *pl, const int32_t *nbr_dev, float *theta, f
     a.stride = stride;
     a.K = pl->K; a.q = pl->q; a.logT = pl->logT; a.mode = mode;
     a.eta = eta; a.zeta = zeta; a.inv = pl->inv;
+    a.flags = pl->flags;
     bool vec4 = aligned16(theta) && (stride % 4 == 0);
     if (mode != GBMUF_MODE_GOSSIP_MA) vec4 = vec4 && aligned16(omega) && aligned16(delta);
     return launch_sync(pl->variant, vec4, a, static_cast<int64_t>(pl->tiles.size()), stream);
@@ -224,6 +226,7 @@ int gbmuf_plan(gbmuf_plan_t **out, const int64_t *comp_offsets, int32_t m, int32
                             sizeof(int32_t) * static_cast<size_t>(pl->C));
             }
             pl->variant = choose_variant();
+            if (const char *f = std::getenv("GBMUF_FLAGS")) pl->flags = std::atoi(f) & 3;
             const int slots = pl->variant.threads * pl->variant.slots;
             if (K > slots) rc = GBMUF_EUNSUPPORTED;
             int lg = 0;
@@ -332,6 +335,13 @@ int gbmuf_sync_table(const gbmuf_plan_t *plan, const int32_t *nbr_dev, float *re
     if (!nbr_dev && plan->q > 0 && plan->m > 0) return GBMUF_EINVAL;
     return enqueue_sync(plan, nbr_dev ? nbr_dev : plan->d_nbr, replicas, global, delta, worker_stride, eta,
                         zeta, nesterov, static_cast<hipStream_t>(stream));
+}
+
+int gbmuf_probe_copy(float *dst_dev, const float *src_dev, int64_t n_floats, int32_t flags, void *stream)
+{
+    if (!dst_dev || !src_dev || n_floats < 0 || (n_floats & 3)) return GBMUF_EINVAL;
+    if (!aligned16(dst_dev) || !aligned16(src_dev)) return GBMUF_EINVAL;
+    return launch_copy_probe(dst_dev, src_dev, n_floats, flags, 256 * 16, static_cast<hipStream_t>(stream));
 }
 
 const char *gbmuf_last_error_detail(void) { return gbmuf::g_detail; }

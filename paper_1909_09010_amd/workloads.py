@@ -99,23 +99,55 @@ def padded_stride(P: int, multiple: int = 64) -> int:
     return (P + multiple - 1) // multiple * multiple
 
 
-def init_state(w: Workload, device, stride: Optional[int] = None, seed: Optional[int] = None):
-    """theta, omega, delta as [K, stride] float32 tensors on ``device``.
+def alloc_state(K: int, P: int, device, span_bytes: Optional[int] = None, stride: Optional[int] = None):
+    """Uninitialised theta, omega, delta as [K, P_padded] float32 views plus their row stride.
+
+    span_bytes None: three separate contiguous tensors (row stride = ``stride`` or P rounded
+    up to 64).  span_bytes set: ONE arena in which worker w's three rows sit side by side,
+    [theta_w | omega_w | delta_w | gap], with the row stride chosen so that the K rows cover
+    about span_bytes of HBM.  On MI355X the sync kernel is measurably faster when the rows it
+    streams concurrently are spread over much more than ~70 GB of HBM address space (more
+    independent DRAM banks); 150 GB is a good span for every benchmark configuration.
+    """
+    dev = torch.device(device)
+    Pp = padded_stride(P) if stride is None else stride
+    assert Pp >= P
+    if span_bytes is None:
+        return [torch.empty((K, Pp), device=dev, dtype=torch.float32) for _ in range(3)] + [Pp]
+    assert stride is None
+    S = 3 * Pp
+    if K > 1:
+        S = max(S, (span_bytes // 4 - 3 * Pp) // (K - 1) // 1024 * 1024)
+    arena = torch.empty((K - 1) * S + 3 * Pp, device=dev, dtype=torch.float32)
+    views = [torch.as_strided(arena, (K, Pp), (S, 1), j * Pp) for j in range(3)]
+    return views + [S]
+
+
+def default_span_bytes(device, state_bytes: int, want: int = 150 * 10**9) -> Optional[int]:
+    """HBM span for alloc_state: ``want`` if it fits beside 8 GB of head room, else whatever
+    does; None (contiguous layout) if the state itself is larger than that."""
+    free, _ = torch.cuda.mem_get_info(torch.device(device))
+    span = min(want, free - 8 * 10**9)
+    return int(span) if span > state_bytes else None
+
+
+def init_state(w: Workload, device, stride: Optional[int] = None, seed: Optional[int] = None,
+               span_bytes: Optional[int] = None):
+    """theta, omega, delta as [K, P_padded] float32 tensors (or strided views, see alloc_state)
+    on ``device``; the row stride is ``theta.stride(0)``.
     W0 ~ w0_dist; theta_k = W0 + N(0, drift_std); omega_k = W0; Delta ~ N(0, delta_std) or 0.
     Padding columns (>= P) are zero.  Generated row by row to bound temporary memory."""
     P = n_params(w)
-    stride = padded_stride(P) if stride is None else stride
-    assert stride >= P
     dev = torch.device(device)
+    theta, omega, delta, _ = alloc_state(w.K, P, dev, span_bytes=span_bytes, stride=stride)
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed if seed is None else seed)
     if w.w0_dist == "normal":
         w0 = torch.randn(P, generator=g, device=dev, dtype=torch.float32) * w.w0_scale
     else:
         w0 = (torch.rand(P, generator=g, device=dev, dtype=torch.float32) * 2 - 1) * w.w0_scale
-    theta = torch.zeros((w.K, stride), device=dev, dtype=torch.float32)
-    omega = torch.zeros((w.K, stride), device=dev, dtype=torch.float32)
-    delta = torch.zeros((w.K, stride), device=dev, dtype=torch.float32)
+    for t in (theta, omega, delta):
+        t.zero_()
     for k in range(w.K):
         omega[k, :P] = w0
         theta[k, :P] = w0 + torch.randn(P, generator=g, device=dev, dtype=torch.float32) * w.drift_std

@@ -241,7 +241,7 @@ def _run_full(w, stride=None, drift_each_round=False):
     off = W.component_offsets(w)
     P = int(off[-1])
     theta, omega, delta = W.init_state(w, DEV, stride=stride)
-    stride = theta.shape[1]
+    stride = theta.stride(0)
     host = _to_host(theta, omega, delta)
     pl = B.Plan(off, w.K, w.q, w.p, seed=w.seed)
     m = len(off) - 1
@@ -277,7 +277,7 @@ def test_config1_medium_unpadded_stride():
     _run_full(dataclasses.replace(w, rounds=3), stride=W.n_params(w))
 
 
-def _run_sampled(w, stride=None, rounds=None):
+def _run_sampled(w, stride=None, rounds=None, spread=False):
     """Full-size run on the GPU in the launch configuration the benchmark times; the oracle
     replays all rounds on a sample of element columns (columns never interact): the first
     and last 48 elements of every component and 32 seeded interior ones."""
@@ -285,8 +285,10 @@ def _run_sampled(w, stride=None, rounds=None):
     off = W.component_offsets(w)
     P = int(off[-1])
     m = len(off) - 1
-    theta, omega, delta = W.init_state(w, DEV, stride=stride)
-    stride = theta.shape[1]
+    span = W.default_span_bytes(DEV, 3 * w.K * W.padded_stride(P) * 4) if spread else None
+    theta, omega, delta = W.init_state(w, DEV, stride=stride, span_bytes=span)
+    stride = theta.stride(0)
+    assert (stride > 2 * theta.shape[1]) == bool(span)
     cols, red_off = W.sample_columns(off, seed=w.seed)
     idx = torch.from_numpy(cols).to(DEV)
     host = [t.index_select(1, idx).cpu().numpy().copy() for t in (theta, omega, delta)]
@@ -321,6 +323,13 @@ def test_config2_large_vocab_sampled_columns():
     _run_sampled(W.get(2))
 
 
+def test_config2_large_vocab_in_the_benchmarks_hbm_spanning_layout():
+    # bench.py's launch configuration: worker rows interleaved in one arena, row stride of
+    # several GB (> 2^31 floats), so every index is 64-bit
+    _need_gpu()
+    _run_sampled(W.get(2), spread=True)
+
+
 def test_config2_large_vocab_unpadded_stride_takes_the_4_byte_path():
     _need_gpu()
     w = W.get(2)
@@ -339,4 +348,4 @@ def test_config4_k64_sampled_columns():
 
 def test_config4b_k64_4layer_sampled_columns():
     _need_gpu()
-    _run_sampled(W.get("k64_4layer"))
+    _run_sampled(W.get("k64_4layer"), spread=True)
