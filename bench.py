@@ -95,6 +95,30 @@ def run_gpu(w, steps: int, warmup: int, contiguous: bool = False):
                 kernel_ms=kernel_ms, finite=finite, layout="contiguous" if span is None else "interleaved_rows")
 
 
+def run_copy_probe(n_floats: int = 1 << 28, launches: int = 3):
+    """gbmuf_probe_copy on two 1 GiB buffers: 4*n bytes read and 4*n bytes written per launch."""
+    import numpy as np
+    import torch
+
+    from paper_1909_09010_amd import binding
+
+    src = torch.randn(n_floats, device="cuda:0")
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream()
+    binding.probe_copy(dst, src, n_floats, 0, stream)
+    pairs = []
+    for _ in range(launches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        binding.probe_copy(dst, src, n_floats, 0, stream)
+        e1.record(stream)
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    ms = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+    assert torch.equal(src, dst)
+    return {"bytes_read": 4 * n_floats, "bytes_written": 4 * n_floats, "ms": ms, "GBps": 8 * n_floats / ms / 1e6}
+
+
 def run_cpu_baseline(w, target_seconds: float = 15.0):
     """The oracle as it stands, on this machine's host cores, on a bounded sample of the workload:
     the leading stripe of every component (same K, q, m, neighbour tables and scalars)."""
@@ -140,6 +164,9 @@ def main() -> int:
                     help="name or index into the benchmark configurations (default: configs[2], large_vocab)")
     ap.add_argument("--all", action="store_true", help="also time configs[1], [3], [4] and the 4-layer K=64 variant")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch the library's plain copy probe (1 GiB read + 1 GiB written per launch): "
+                         "the known-traffic kernel that rocprofv3 byte counters are scaled by")
     ap.add_argument("--contiguous", action="store_true",
                     help="three separate contiguous [K, P] tensors instead of the HBM-spanning row layout")
     args = ap.parse_args()
@@ -200,6 +227,8 @@ def main() -> int:
                            "effective_GBps": BYTES_PER_WORKER_PARAM * v / 1e9, "kernel_GBps": kb,
                            "kernel_frac": kb / HBM_PEAK_GBPS})
         out["other_workloads"] = others
+    if args.calibrate:
+        out["copy_probe"] = run_copy_probe()
     if not args.no_cpu:
         out["cpu_baseline"] = run_cpu_baseline(w)
     print(json.dumps(out), flush=True)
