@@ -153,6 +153,34 @@ int gbmuf_sync_table(const gbmuf_plan_t *plan, const int32_t *nbr_dev, float *re
                      float zeta, int32_t nesterov, void *stream);
 
 /*
+ * Per-component synchronisation periods (Algorithm 1: component i takes the sync branch only
+ * when t mod H_i == 0; Section 3.3 uses (16,128): embedding shards every 128 mini-batches,
+ * the rest every 16).
+ * gbmuf_plan_set_periods stores H_i >= 1 for the m components (host array, copied; NULL
+ * clears them, i.e. every component syncs).  It synchronises the device and must not run
+ * concurrently with syncs on the same plan.  EINVAL for NULL plan or H_i < 1.
+ * gbmuf_sync_step is gbmuf_sync for mini-batch counter `step`: only the components with
+ * step mod H_i == 0 are updated, the others are not read or written; the neighbour tables
+ * are those of round = step, so every sync of every component draws fresh neighbours
+ * (Section 2.2, last paragraph).  Without periods it equals gbmuf_sync(round = step).
+ * Contiguous runs of active components are launched as ranges of the tile list (up to 8
+ * runs); a more scattered schedule takes one launch that checks the period on the device.
+ */
+int gbmuf_plan_set_periods(gbmuf_plan_t *plan, const int32_t *periods_host);
+int gbmuf_sync_step(const gbmuf_plan_t *plan, float *replicas, float *global, float *delta,
+                    int64_t worker_stride, float eta, float zeta, int32_t nesterov,
+                    uint64_t step, void *stream);
+
+/*
+ * Final model of Algorithm 1 (RETURN statement): out_dev[e] = (1/K) * sum_k replicas[k][e]
+ * for e < P, summed in ascending worker id and multiplied by the rounded constant 1/K.
+ * replicas: device, K rows of worker_stride floats (read only); out_dev: device, P floats.
+ * 16-byte aligned pointers with worker_stride % 4 == 0 take 16-byte loads.
+ */
+int gbmuf_final_average(const gbmuf_plan_t *plan, const float *replicas, int64_t worker_stride,
+                        float *out_dev, void *stream);
+
+/*
  * Calibration probe, not part of the method: a plain streaming copy of n_floats floats
  * (a multiple of 4; both pointers device memory, 16-byte aligned, not overlapping) with
  * one read and one write per byte.  It gives hardware byte counters a launch of known

@@ -51,6 +51,11 @@ def _load() -> ctypes.CDLL:
     L.gbmuf_neighbours_device.argtypes = [vp, u64, vp, vp]
     L.gbmuf_sync.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, u64, vp]
     L.gbmuf_sync_table.argtypes = [vp, vp, vp, vp, vp, i64, f32, f32, i32, vp]
+    L.gbmuf_plan_set_periods.argtypes = [vp, vp]
+    L.gbmuf_sync_step.argtypes = [vp, vp, vp, vp, i64, f32, f32, i32, u64, vp]
+    L.gbmuf_final_average.argtypes = [vp, vp, i64, vp, vp]
+    for name in ("gbmuf_plan_set_periods", "gbmuf_sync_step", "gbmuf_final_average"):
+        getattr(L, name).restype = ctypes.c_int
     L.gbmuf_probe_copy.argtypes = [vp, vp, i64, i32, vp]
     L.gbmuf_probe_copy.restype = ctypes.c_int
     L.gbmuf_strerror.argtypes = [ctypes.c_int]
@@ -154,6 +159,29 @@ class Plan:
                              nesterov, round, _stream(stream))
         if rc != GBMUF_OK:
             raise GbmufError(rc, "gbmuf_sync")
+
+    def set_periods(self, periods_host) -> None:
+        if periods_host is None:
+            rc = _lib.gbmuf_plan_set_periods(self._h, None)
+        else:
+            h = np.ascontiguousarray(periods_host, dtype=np.int32)
+            if h.shape != (self.info.m,):
+                raise GbmufError(GBMUF_EINVAL, "gbmuf_plan_set_periods")
+            rc = _lib.gbmuf_plan_set_periods(self._h, h.ctypes.data_as(ctypes.c_void_p))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_plan_set_periods")
+
+    def sync_step(self, replicas, global_, delta, worker_stride: int, eta: float, zeta: float,
+                  nesterov: int = MODE_PAPER, step: int = 0, stream=None) -> None:
+        rc = _lib.gbmuf_sync_step(self._h, _dev(replicas), _dev(global_), _dev(delta), worker_stride, eta, zeta,
+                                  nesterov, step, _stream(stream))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_sync_step")
+
+    def final_average(self, replicas, worker_stride: int, out_dev, stream=None) -> None:
+        rc = _lib.gbmuf_final_average(self._h, _dev(replicas), worker_stride, _dev(out_dev), _stream(stream))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_final_average")
 
     def sync_table(self, nbr_dev, replicas, global_, delta, worker_stride: int, eta: float, zeta: float,
                    nesterov: int = MODE_PAPER, stream=None) -> None:

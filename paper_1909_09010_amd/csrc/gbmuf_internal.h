@@ -29,6 +29,8 @@ struct SyncArgs {
     int32_t mode;            // GBMUF_MODE_*
     float eta, zeta, inv;    // inv = 1/(q+1), rounded once on the host
     int32_t flags;           // bit 0: streaming (nontemporal) stores, bit 1: streaming loads
+    const int32_t *periods;  // per-component sync period H_i, or nullptr: every component syncs
+    uint64_t step;           // with periods: component i syncs iff step % H_i == 0
 };
 
 // Arguments of the neighbour-sampling kernel.
@@ -108,6 +110,8 @@ int hip_failed(const char *what, hipError_t err, int status);
 
 // kernels.hip
 int launch_sampler(const SampleArgs &a, hipStream_t stream);
+int launch_final_average(const float *theta, int64_t stride, int K, int64_t P, float inv, float *out,
+                         hipStream_t stream);
 int launch_copy_probe(float *dst, const float *src, int64_t n_floats, int flags, int blocks, hipStream_t stream);
 int launch_sync(const Variant &v, bool vec4, const SyncArgs &a, int64_t n_tiles, hipStream_t stream);
 int prepare_kernels(const Variant &v, int K, int q, size_t *lds_bytes_out);

@@ -116,6 +116,7 @@ __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
 
     const int tid = threadIdx.x;
     const TileDesc td = a.tiles[blockIdx.x];
+    if (a.periods != nullptr && a.step % static_cast<uint64_t>(a.periods[td.comp]) != 0) return;  // whole workgroup
     const int K = a.K, q = a.q, q1 = (Q1 > 0) ? Q1 : a.q + 1;
     const int logT = a.logT, T = 1 << logT;
     const int mode = a.mode;
@@ -210,6 +211,41 @@ __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Final model average (Algorithm 1, RETURN): out[e] = fl(1/K) * (theta[0][e] + theta[1][e] + ...),
+// summed in ascending worker id.  One thread per 16-byte column; 4(K+1) bytes per parameter.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void final_average_vec4_kernel(const float *theta, int64_t stride, int K,
+                                                                 int64_t P, float inv, float *out)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t n4 = P >> 2;
+    if (i < n4) {
+        const float *col = theta + (i << 2);
+        v4f s = *reinterpret_cast<const v4f *>(col);
+#pragma unroll 4
+        for (int k = 1; k < K; ++k) s = s + *reinterpret_cast<const v4f *>(col + static_cast<int64_t>(k) * stride);
+        *reinterpret_cast<v4f *>(out + (i << 2)) = s * inv;
+    } else if (i == n4) {                                  // the last P % 4 elements
+        for (int64_t e = n4 << 2; e < P; ++e) {
+            float s = theta[e];
+            for (int k = 1; k < K; ++k) s = s + theta[static_cast<int64_t>(k) * stride + e];
+            out[e] = s * inv;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void final_average_vec1_kernel(const float *theta, int64_t stride, int K,
+                                                                 int64_t P, float inv, float *out)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= P) return;
+    float s = theta[e];
+#pragma unroll 4
+    for (int k = 1; k < K; ++k) s = s + theta[static_cast<int64_t>(k) * stride + e];
+    out[e] = s * inv;
+}
+
 // Plain streaming copy of n 16-byte words (calibration of HBM counters and a reference for
 // the bandwidth a 1:1 read/write stream reaches on this device).
 __global__ __launch_bounds__(256) void copy_probe_kernel(v4f *dst, const v4f *src, int64_t n, int flags)
@@ -235,6 +271,7 @@ __global__ __launch_bounds__(NT) void sync_vec1_kernel(SyncArgs a)
 
     const int tid = threadIdx.x;
     const TileDesc td = a.tiles[blockIdx.x];
+    if (a.periods != nullptr && a.step % static_cast<uint64_t>(a.periods[td.comp]) != 0) return;  // whole workgroup
     const int K = a.K, q = a.q, q1 = a.q + 1;
     const int logT = a.logT, T = 1 << logT;
     const int mode = a.mode;
@@ -283,6 +320,7 @@ __global__ __launch_bounds__(NT) void sync_vec1_kernel(SyncArgs a)
 
 constexpr Variant kVariants[] = {
     {256, 8}, {512, 8}, {512, 4}, {256, 16}, {1024, 4}, {256, 4},
+    {256, 2}, {512, 2}, {1024, 2}, {1024, 1}, {512, 1}, {256, 1},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -311,6 +349,12 @@ KernelFn pick_kernel(const Variant &v, bool vec4, int q1)
     GBMUF_CASE(256, 16)
     GBMUF_CASE(1024, 4)
     GBMUF_CASE(256, 4)
+    GBMUF_CASE(256, 2)
+    GBMUF_CASE(512, 2)
+    GBMUF_CASE(1024, 2)
+    GBMUF_CASE(1024, 1)
+    GBMUF_CASE(512, 1)
+    GBMUF_CASE(256, 1)
 #undef GBMUF_CASE
     return nullptr;
 }
@@ -366,6 +410,22 @@ int launch_sync(const Variant &v, bool vec4, const SyncArgs &a, int64_t n_tiles,
     const hipError_t err = hipLaunchKernel(reinterpret_cast<const void *>(k), dim3(static_cast<unsigned>(n_tiles)),
                                            dim3(v.threads), argv, lds, stream);
     return err == hipSuccess ? GBMUF_OK : hip_failed("hipLaunchKernel(sync)", err, GBMUF_EDEVICE);
+}
+
+int launch_final_average(const float *theta, int64_t stride, int K, int64_t P, float inv, float *out,
+                         hipStream_t stream)
+{
+    if (P <= 0) return GBMUF_OK;
+    const bool vec4 = ((reinterpret_cast<uintptr_t>(theta) | reinterpret_cast<uintptr_t>(out)) & 15u) == 0 &&
+                      stride % 4 == 0;
+    const int64_t threads = vec4 ? (P >> 2) + 1 : P;
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffLL) return GBMUF_EUNSUPPORTED;
+    void *argv[] = {&theta, &stride, &K, &P, &inv, &out};
+    const void *fn = vec4 ? reinterpret_cast<const void *>(final_average_vec4_kernel)
+                          : reinterpret_cast<const void *>(final_average_vec1_kernel);
+    const hipError_t err = hipLaunchKernel(fn, dim3(static_cast<unsigned>(blocks)), dim3(256), argv, 0, stream);
+    return err == hipSuccess ? GBMUF_OK : hip_failed("hipLaunchKernel(final average)", err, GBMUF_EDEVICE);
 }
 
 int launch_copy_probe(float *dst, const float *src, int64_t n_floats, int flags, int blocks, hipStream_t stream)

@@ -18,7 +18,9 @@ struct gbmuf_plan_s {
     int64_t P = 0;
     std::vector<int64_t> off;        // m+1 component offsets
     std::vector<int32_t> cand;       // [K][C] ring candidates, order of Definition 1
-    std::vector<TileDesc> tiles;     // work list of the fused kernel
+    std::vector<TileDesc> tiles;     // work list of the fused kernel, in component order
+    std::vector<int64_t> tile_start; // m+1: first tile of every component
+    std::vector<int32_t> periods;    // per-component sync period H_i (empty: all 1)
     Variant variant{256, 8};
     int32_t logT = 0;
     float inv = 1.0f;                // 1/(q+1), rounded once
@@ -29,6 +31,7 @@ struct gbmuf_plan_s {
     int32_t *d_cand = nullptr;
     TileDesc *d_tiles = nullptr;
     int32_t *d_nbr = nullptr;        // neighbour scratch of gbmuf_sync, [m][K][q]
+    int32_t *d_periods = nullptr;    // m entries, valid when periods is not empty
 };
 
 namespace gbmuf {
@@ -72,11 +75,18 @@ struct HostPerm {
     int32_t &operator()(int32_t x) const { return base[x]; }
 };
 
-const Variant &choose_variant()
+// Tile shape.  Measured on MI355X (large states, HBM-spanning layout): short tiles of about
+// 32 columns (512 B per worker row) with few 16-byte slots per thread run fastest, 75-77 % of
+// peak; K > 32 needs 1024 threads to keep the columns that wide.  GBMUF_VARIANT overrides.
+const Variant &choose_variant(int K)
 {
     int count = 0;
     const Variant *tab = variant_table(&count);
+    const int want_threads = K <= 32 ? 256 : 1024;
+    const int want_slots = K <= 8 ? 1 : K <= 16 ? 2 : 4;
     int pick = 0;
+    for (int i = 0; i < count; ++i)
+        if (tab[i].threads == want_threads && tab[i].slots == want_slots) pick = i;
     if (const char *s = std::getenv("GBMUF_VARIANT")) {
         const int v = std::atoi(s);
         if (v >= 0 && v < count) pick = v;
@@ -89,8 +99,11 @@ void build_tiles(gbmuf_plan_s &pl)
 {
     const int64_t T = static_cast<int64_t>(1) << pl.logT;
     pl.tiles.clear();
+    pl.tile_start.assign(static_cast<size_t>(pl.m) + 1, 0);
     for (int32_t i = 0; i < pl.m; ++i) {
         const int64_t a = pl.off[static_cast<size_t>(i)], b = pl.off[static_cast<size_t>(i) + 1];
+        pl.tile_start[static_cast<size_t>(i)] = static_cast<int64_t>(pl.tiles.size());
+        pl.tile_start[static_cast<size_t>(i) + 1] = static_cast<int64_t>(pl.tiles.size());
         if (a >= b) continue;
         const int64_t ga = a >> 2, gb = (b + 3) >> 2;
         for (int64_t g = ga; g < gb; g += T) {
@@ -98,6 +111,7 @@ void build_tiles(gbmuf_plan_s &pl)
             const int64_t end = ((g + T) << 2) < b ? ((g + T) << 2) : b;
             pl.tiles.push_back(TileDesc{lo, static_cast<int32_t>(end - lo), i});
         }
+        pl.tile_start[static_cast<size_t>(i) + 1] = static_cast<int64_t>(pl.tiles.size());
     }
 }
 
@@ -106,7 +120,8 @@ void free_device(gbmuf_plan_s &pl)
     if (pl.d_cand) (void)hipFree(pl.d_cand);
     if (pl.d_tiles) (void)hipFree(pl.d_tiles);
     if (pl.d_nbr) (void)hipFree(pl.d_nbr);
-    pl.d_cand = nullptr; pl.d_tiles = nullptr; pl.d_nbr = nullptr;
+    if (pl.d_periods) (void)hipFree(pl.d_periods);
+    pl.d_cand = nullptr; pl.d_tiles = nullptr; pl.d_nbr = nullptr; pl.d_periods = nullptr;
 }
 
 template <class T>
@@ -144,6 +159,11 @@ int make_device_state(gbmuf_plan_s &pl)
         pl.d_nbr = nullptr;
         return hip_failed("hipMalloc(neighbour scratch)", err, GBMUF_ENOMEM);
     }
+    err = hipMalloc(reinterpret_cast<void **>(&pl.d_periods), (pl.m ? pl.m : 1) * sizeof(int32_t));
+    if (err != hipSuccess) {
+        pl.d_periods = nullptr;
+        return hip_failed("hipMalloc(periods)", err, GBMUF_ENOMEM);
+    }
     pl.has_device = true;
     return GBMUF_OK;
 }
@@ -151,10 +171,14 @@ int make_device_state(gbmuf_plan_s &pl)
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int enqueue_sync(const gbmuf_plan_s *pl, const int32_t *nbr_dev, float *theta, float *omega, float *delta,
-                 int64_t stride, float eta, float zeta, int32_t mode, hipStream_t stream)
+                 int64_t stride, float eta, float zeta, int32_t mode, hipStream_t stream,
+                 int64_t first_tile = 0, int64_t n_tiles = -1, bool check_periods = false, uint64_t step = 0)
 {
+    if (n_tiles < 0) n_tiles = static_cast<int64_t>(pl->tiles.size());
     SyncArgs a{};
-    a.tiles = pl->d_tiles;
+    a.tiles = pl->d_tiles + first_tile;
+    a.periods = check_periods ? pl->d_periods : nullptr;
+    a.step = step;
     a.nbr = nbr_dev;
     a.theta = theta; a.omega = omega; a.delta = delta;
     a.stride = stride;
@@ -163,7 +187,7 @@ int enqueue_sync(const gbmuf_plan_s *pl, const int32_t *nbr_dev, float *theta, f
     a.flags = pl->flags;
     bool vec4 = aligned16(theta) && (stride % 4 == 0);
     if (mode != GBMUF_MODE_GOSSIP_MA) vec4 = vec4 && aligned16(omega) && aligned16(delta);
-    return launch_sync(pl->variant, vec4, a, static_cast<int64_t>(pl->tiles.size()), stream);
+    return launch_sync(pl->variant, vec4, a, n_tiles, stream);
 }
 
 int check_sync(const gbmuf_plan_s *pl, const float *theta, const float *omega, const float *delta,
@@ -225,7 +249,7 @@ int gbmuf_plan(gbmuf_plan_t **out, const int64_t *comp_offsets, int32_t m, int32
                 std::memcpy(pl->cand.data() + static_cast<size_t>(w) * pl->C, ring.data(),
                             sizeof(int32_t) * static_cast<size_t>(pl->C));
             }
-            pl->variant = choose_variant();
+            pl->variant = choose_variant(K);
             if (const char *f = std::getenv("GBMUF_FLAGS")) pl->flags = std::atoi(f) & 3;
             const int slots = pl->variant.threads * pl->variant.slots;
             if (K > slots) rc = GBMUF_EUNSUPPORTED;
@@ -325,6 +349,81 @@ int gbmuf_sync(const gbmuf_plan_t *plan, float *replicas, float *global, float *
     rc = launch_sampler(sample_args(plan, round, plan->d_nbr), s);
     if (rc != GBMUF_OK) return rc;
     return enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s);
+}
+
+int gbmuf_plan_set_periods(gbmuf_plan_t *plan, const int32_t *periods_host)
+{
+    if (!plan) return GBMUF_EINVAL;
+    if (!periods_host) {
+        plan->periods.clear();
+        return GBMUF_OK;
+    }
+    for (int32_t i = 0; i < plan->m; ++i)
+        if (periods_host[i] < 1) return GBMUF_EINVAL;
+    try {
+        plan->periods.assign(periods_host, periods_host + plan->m);
+    } catch (const std::bad_alloc &) {
+        return GBMUF_ENOMEM;
+    }
+    if (plan->has_device && plan->m > 0) {
+        // ordered after everything already enqueued on the device, and complete on return
+        hipError_t err = hipDeviceSynchronize();
+        if (err == hipSuccess)
+            err = hipMemcpy(plan->d_periods, plan->periods.data(), sizeof(int32_t) * static_cast<size_t>(plan->m),
+                            hipMemcpyHostToDevice);
+        if (err != hipSuccess) return hip_failed("hipMemcpy(periods)", err, GBMUF_EDEVICE);
+    }
+    return GBMUF_OK;
+}
+
+int gbmuf_sync_step(const gbmuf_plan_t *plan, float *replicas, float *global, float *delta, int64_t worker_stride,
+                    float eta, float zeta, int32_t nesterov, uint64_t step, void *stream)
+{
+    int rc = check_sync(plan, replicas, global, delta, worker_stride, nesterov);
+    if (rc != GBMUF_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->periods.empty())
+        return gbmuf_sync(plan, replicas, global, delta, worker_stride, eta, zeta, nesterov, step, stream);
+    // runs of consecutive components that sync at this step = contiguous ranges of the tile list
+    struct Run { int64_t first, count; };
+    Run runs[8];
+    int n_runs = 0;
+    bool too_many = false, any = false;
+    for (int32_t i = 0; i < plan->m; ++i) {
+        const bool active = step % static_cast<uint64_t>(plan->periods[static_cast<size_t>(i)]) == 0;
+        const int64_t t0 = plan->tile_start[static_cast<size_t>(i)], t1 = plan->tile_start[static_cast<size_t>(i) + 1];
+        if (!active || t1 == t0) continue;
+        any = true;
+        if (n_runs > 0 && runs[n_runs - 1].first + runs[n_runs - 1].count == t0) {
+            runs[n_runs - 1].count += t1 - t0;
+        } else if (n_runs < 8) {
+            runs[n_runs++] = Run{t0, t1 - t0};
+        } else {
+            too_many = true;
+            break;
+        }
+    }
+    if (!any) return GBMUF_OK;
+    rc = launch_sampler(sample_args(plan, step, plan->d_nbr), s);
+    if (rc != GBMUF_OK) return rc;
+    if (too_many)                                           // scattered schedule: one launch, checked on the device
+        return enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s, 0, -1,
+                            true, step);
+    for (int r = 0; r < n_runs; ++r) {
+        rc = enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s,
+                          runs[r].first, runs[r].count);
+        if (rc != GBMUF_OK) return rc;
+    }
+    return GBMUF_OK;
+}
+
+int gbmuf_final_average(const gbmuf_plan_t *plan, const float *replicas, int64_t worker_stride, float *out_dev,
+                        void *stream)
+{
+    if (!plan || !replicas || !out_dev || worker_stride < plan->P) return GBMUF_EINVAL;
+    if (!plan->has_device) return GBMUF_EDEVICE;
+    return launch_final_average(replicas, worker_stride, plan->K, plan->P, 1.0f / static_cast<float>(plan->K), out_dev,
+                                static_cast<hipStream_t>(stream));
 }
 
 int gbmuf_sync_table(const gbmuf_plan_t *plan, const int32_t *nbr_dev, float *replicas, float *global,

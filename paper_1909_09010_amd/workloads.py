@@ -38,6 +38,7 @@ class Workload:
     delta_std: float            # Delta init std (0 = zeros)
     seed: int
     p: int = 0                  # 0 = paper's rule p = log2(K) - 1
+    kind: str = "lstm_lm"       # "lstm_lm": plain LSTM LM with full softmax; "paper": Section 3.2's model
 
 
 # The five benchmark configurations (index = position in BASELINE.json's list) and "4b",
@@ -53,6 +54,17 @@ WORKLOADS = {
     "k64_4layer": Workload("k64_4layer", 64, 4, 50000, 1024, 1024, 4, 1024, 0.95, 1.0, 1, 10,
                            "normal", 0.02, 0.01, 1e-4, 4),
 }
+# The paper's own model and partition (Section 3.2): embedding 512 in 8 even shards, one LSTMP
+# layer 2048/512 (LSTM weights one group, projection weights another), adaptive softmax with a
+# head of 8192 words and 5 tails (projection factor 2), each tail its own group: 16 components;
+# 16 workers with (p, q) = (3, 2) and sync periods (16, 128) (Section 3.3).  Tail sizes are not
+# given in the paper; the remaining 259,543 words are split 16384/32768/49152/65536/95703.
+WORKLOADS["paper_shaped"] = Workload("paper_shaped", 16, 2, 267735, 512, 2048, 1, None, 0.9, 1.0, 1, 16,
+                                     "normal", 0.02, 0.005, 0.0, 5, 3, "paper")
+PAPER_TAILS = (16384, 32768, 49152, 65536, 95703)
+PAPER_HEAD = 8192
+PAPER_PROJ = 512
+
 CONFIG_ORDER = ["tiny", "medium", "large_vocab", "large_vocab_chunked", "k64"]
 
 
@@ -69,6 +81,16 @@ def scaled(w: Workload, vocab: int) -> Workload:
 
 def tensors(w: Workload) -> List[Tuple[str, int, int]]:
     """(name, rows, cols) of the flat parameter vector, in order.  cols = 1 for vectors."""
+    if w.kind == "paper":
+        out = [("embedding", w.vocab, w.embed),
+               ("lstm.W+b", (w.embed + PAPER_PROJ) * 4 * w.hidden + 4 * w.hidden, 1),
+               ("lstmp.projection", w.hidden, PAPER_PROJ),
+               ("asm.head", PAPER_PROJ, PAPER_HEAD + len(PAPER_TAILS))]
+        for i, n in enumerate(PAPER_TAILS, start=1):
+            d = PAPER_PROJ >> i
+            out.append((f"asm.tail{i}", PAPER_PROJ * d + d * n, 1))
+        assert PAPER_HEAD + sum(PAPER_TAILS) == w.vocab
+        return out
     out = [("embedding", w.vocab, w.embed)]
     for layer in range(w.layers):
         n_in = w.embed if layer == 0 else w.hidden
@@ -82,6 +104,14 @@ def component_offsets(w: Workload) -> np.ndarray:
     """Element offsets of the components (m+1 entries).  Matrices are cut into chunks of
     ``chunk_rows`` rows when set; vectors stay whole."""
     sizes: List[int] = []
+    if w.kind == "paper":
+        for name, rows, cols in tensors(w):
+            if name == "embedding":
+                assert rows * cols % 8 == 0
+                sizes += [rows * cols // 8] * 8
+            else:
+                sizes.append(rows * cols)
+        return np.concatenate([[0], np.cumsum(np.asarray(sizes, dtype=np.int64))]).astype(np.int64)
     for _, rows, cols in tensors(w):
         if w.chunk_rows is None or cols == 1:
             sizes.append(rows * cols)
@@ -89,6 +119,17 @@ def component_offsets(w: Workload) -> np.ndarray:
             for r0 in range(0, rows, w.chunk_rows):
                 sizes.append((min(rows, r0 + w.chunk_rows) - r0) * cols)
     return np.concatenate([[0], np.cumsum(np.asarray(sizes, dtype=np.int64))]).astype(np.int64)
+
+
+def periods(w: Workload) -> Optional[np.ndarray]:
+    """Per-component sync periods H_i, or None when every component syncs at every call.
+    The paper-shaped workload uses Section 3.3's (16, 128): embedding shards 128, others 16."""
+    if w.kind != "paper":
+        return None
+    m = len(component_offsets(w)) - 1
+    h = np.full(m, 16, dtype=np.int32)
+    h[:8] = 128
+    return h
 
 
 def n_params(w: Workload) -> int:

@@ -94,6 +94,28 @@ def test_bad_plans_are_rejected():
     assert L.gbmuf_plan_info(None, None) == B.GBMUF_EINVAL
 
 
+def test_periods_are_validated_on_the_host():
+    pl = B.Plan([0, 4, 10, 10], K=4, q=1)
+    pl.set_periods([16, 128, 1])
+    pl.set_periods(None)
+    with pytest.raises(B.GbmufError) as e:
+        pl.set_periods([16, 0, 1])
+    assert e.value.code == B.GBMUF_EINVAL
+    with pytest.raises(B.GbmufError):
+        pl.set_periods([1, 2])                      # wrong length is caught by the binding
+    assert B.lib().gbmuf_plan_set_periods(None, None) == B.GBMUF_EINVAL
+
+
+def test_paper_shaped_partition_has_16_components():
+    w = W.get("paper_shaped")
+    off = W.component_offsets(w)
+    assert len(off) - 1 == 16 and off[-1] == W.n_params(w)
+    assert len({int(x) for x in (off[1:9] - off[:8])}) == 1       # embedding in 8 even shards (Section 3.2)
+    assert W.periods(w).tolist() == [128] * 8 + [16] * 8          # Section 3.3's (16,128)
+    pl = B.Plan(off, w.K, w.q, w.p, seed=0)
+    assert (pl.info.K, pl.info.p, pl.info.q) == (16, 3, 2)         # Section 3.3, 16 GPUs
+
+
 def test_empty_models_make_empty_plans():
     pl = B.Plan([0], K=4, q=1)
     assert pl.info.m == 0 and pl.info.n_tiles == 0 and pl.neighbours_host(0).size == 0
