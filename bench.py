@@ -61,14 +61,29 @@ def run_gpu(w, steps: int, warmup: int, contiguous: bool = False):
         f"HBM span {(w.K - 1) * stride * 4 / 1e9 + 3 * theta.shape[1] * 4 / 1e9:.0f} GB, init {time.perf_counter() - t0:.1f}s")
     stream = torch.cuda.current_stream()
 
+    H = workloads.periods(w)
+    if H is not None:
+        plan.set_periods(H)                     # Algorithm 1's per-component periods; a step is then one
+        tick = int(H.min())                     # sync of the components that are due (counter += min H_i)
+
     rnd = 0
     for _ in range(warmup):
-        plan.sync(theta, omega, delta, stride, w.eta, w.zeta, w.mode, rnd, stream)
+        if H is None:
+            plan.sync(theta, omega, delta, stride, w.eta, w.zeta, w.mode, rnd, stream)
+        else:
+            plan.sync_step(theta, omega, delta, stride, w.eta, w.zeta, w.mode, (rnd + 1) * tick, stream)
         rnd += 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    synced = 0
     for _ in range(steps):
-        plan.sync(theta, omega, delta, stride, w.eta, w.zeta, w.mode, rnd, stream)
+        if H is None:
+            plan.sync(theta, omega, delta, stride, w.eta, w.zeta, w.mode, rnd, stream)
+            synced += P
+        else:
+            plan.sync_step(theta, omega, delta, stride, w.eta, w.zeta, w.mode, (rnd + 1) * tick, stream)
+            active = ((rnd + 1) * tick) % H == 0
+            synced += int((off[1:] - off[:-1])[active].sum())
         rnd += 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -91,7 +106,7 @@ def run_gpu(w, steps: int, warmup: int, contiguous: bool = False):
     plan.destroy()
     del theta, omega, delta, nbr
     torch.cuda.empty_cache()
-    return dict(P=P, m=m, K=w.K, stride=stride, padded=workloads.padded_stride(P), elapsed=elapsed,
+    return dict(P=P, m=m, K=w.K, stride=stride, synced_per_step=synced / max(steps, 1), padded=workloads.padded_stride(P), elapsed=elapsed,
                 kernel_ms=kernel_ms, finite=finite, layout="contiguous" if span is None else "interleaved_rows")
 
 
@@ -215,13 +230,13 @@ def main() -> int:
     }
     if args.all:
         others = []
-        for name in ("medium", "large_vocab_chunked", "k64", "k64_4layer"):
+        for name in ("tiny", "medium", "large_vocab_chunked", "k64", "k64_4layer", "paper_shaped"):
             if name == w.name:
                 continue
             ww = workloads.get(name)
             steps = min(args.steps, ww.rounds)
             gg = run_gpu(ww, steps, args.warmup, args.contiguous)
-            v = gg["K"] * gg["P"] * steps / gg["elapsed"]
+            v = gg["K"] * gg["synced_per_step"] * steps / gg["elapsed"]   # worker-params actually synced
             kb = BYTES_PER_WORKER_PARAM * gg["K"] * gg["P"] / (gg["kernel_ms"] * 1e-3) / 1e9
             others.append({"workload": name, "value": v, "ms_per_step": gg["elapsed"] / steps * 1e3,
                            "effective_GBps": BYTES_PER_WORKER_PARAM * v / 1e9, "kernel_GBps": kb,

@@ -181,6 +181,28 @@ int gbmuf_final_average(const gbmuf_plan_t *plan, const float *replicas, int64_t
                         float *out_dev, void *stream);
 
 /*
+ * Placement advice for the three state buffers (host only, no GPU needed).  The ABI takes
+ * three base pointers and one row stride, so rows may be placed anywhere; on MI355X the
+ * sync kernel is measurably faster (about 62 % -> 75 % of peak HBM bandwidth) when the 3K
+ * rows it streams concurrently are spread over much more than ~70 GB of HBM instead of
+ * sitting side by side.  The layout returned is ONE arena of arena_floats floats holding
+ * [theta_w | omega_w | delta_w | gap] for w = 0..K-1:
+ *     theta = arena, omega = arena + omega_offset, delta = arena + delta_offset,
+ *     row w of each at + w * worker_stride.
+ * span_bytes is the HBM the K rows should cover (e.g. 150e9 on a 288 GB device); the stride
+ * is never smaller than three padded rows, so span_bytes = 0 gives the dense interleaving.
+ * Rows are padded to a multiple of 64 floats and the stride to a multiple of 1024.
+ * EINVAL for P < 0, K < 1, span_bytes < 0 or NULL out.
+ */
+typedef struct gbmuf_layout {
+    int64_t worker_stride;   /* floats between consecutive workers' rows          */
+    int64_t omega_offset;    /* floats from the arena start to omega's first row  */
+    int64_t delta_offset;    /* floats from the arena start to delta's first row  */
+    int64_t arena_floats;    /* floats to allocate                                */
+} gbmuf_layout_t;
+int gbmuf_recommend_layout(int64_t P, int32_t K, int64_t span_bytes, gbmuf_layout_t *out);
+
+/*
  * Calibration probe, not part of the method: a plain streaming copy of n_floats floats
  * (a multiple of 4; both pointers device memory, 16-byte aligned, not overlapping) with
  * one read and one write per byte.  It gives hardware byte counters a launch of known

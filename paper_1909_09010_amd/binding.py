@@ -36,6 +36,11 @@ class Info(ctypes.Structure):
                 ("seed", ctypes.c_uint64)]
 
 
+class Layout(ctypes.Structure):
+    _fields_ = [("worker_stride", ctypes.c_int64), ("omega_offset", ctypes.c_int64),
+                ("delta_offset", ctypes.c_int64), ("arena_floats", ctypes.c_int64)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
@@ -56,6 +61,8 @@ def _load() -> ctypes.CDLL:
     L.gbmuf_final_average.argtypes = [vp, vp, i64, vp, vp]
     for name in ("gbmuf_plan_set_periods", "gbmuf_sync_step", "gbmuf_final_average"):
         getattr(L, name).restype = ctypes.c_int
+    L.gbmuf_recommend_layout.argtypes = [i64, i32, i64, ctypes.POINTER(Layout)]
+    L.gbmuf_recommend_layout.restype = ctypes.c_int
     L.gbmuf_probe_copy.argtypes = [vp, vp, i64, i32, vp]
     L.gbmuf_probe_copy.restype = ctypes.c_int
     L.gbmuf_strerror.argtypes = [ctypes.c_int]
@@ -93,6 +100,14 @@ def _stream(s) -> Optional[int]:
     if hasattr(s, "cuda_stream"):
         return int(s.cuda_stream) or None
     return int(s) or None
+
+
+def recommend_layout(P: int, K: int, span_bytes: int) -> Layout:
+    out = Layout()
+    rc = _lib.gbmuf_recommend_layout(P, K, span_bytes, ctypes.byref(out))
+    if rc != GBMUF_OK:
+        raise GbmufError(rc, "gbmuf_recommend_layout")
+    return out
 
 
 def probe_copy(dst_dev, src_dev, n_floats: int, flags: int = 0, stream=None) -> None:

@@ -436,6 +436,22 @@ int gbmuf_sync_table(const gbmuf_plan_t *plan, const int32_t *nbr_dev, float *re
                         zeta, nesterov, static_cast<hipStream_t>(stream));
 }
 
+int gbmuf_recommend_layout(int64_t P, int32_t K, int64_t span_bytes, gbmuf_layout_t *out)
+{
+    if (!out || P < 0 || K < 1 || span_bytes < 0) return GBMUF_EINVAL;
+    const int64_t row = (P + 63) / 64 * 64;
+    int64_t stride = 3 * row;
+    if (K > 1) {
+        const int64_t spread = (span_bytes / 4 - 3 * row) / (K - 1) / 1024 * 1024;
+        if (spread > stride) stride = spread;
+    }
+    out->worker_stride = stride;
+    out->omega_offset = row;
+    out->delta_offset = 2 * row;
+    out->arena_floats = static_cast<int64_t>(K - 1) * stride + 3 * row;
+    return GBMUF_OK;
+}
+
 int gbmuf_probe_copy(float *dst_dev, const float *src_dev, int64_t n_floats, int32_t flags, void *stream)
 {
     if (!dst_dev || !src_dev || n_floats < 0 || (n_floats & 3)) return GBMUF_EINVAL;

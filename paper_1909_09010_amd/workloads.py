@@ -156,11 +156,11 @@ def alloc_state(K: int, P: int, device, span_bytes: Optional[int] = None, stride
     if span_bytes is None:
         return [torch.empty((K, Pp), device=dev, dtype=torch.float32) for _ in range(3)] + [Pp]
     assert stride is None
-    S = 3 * Pp
-    if K > 1:
-        S = max(S, (span_bytes // 4 - 3 * Pp) // (K - 1) // 1024 * 1024)
-    arena = torch.empty((K - 1) * S + 3 * Pp, device=dev, dtype=torch.float32)
-    views = [torch.as_strided(arena, (K, Pp), (S, 1), j * Pp) for j in range(3)]
+    from . import binding                       # the layout rule lives in the library
+    lay = binding.recommend_layout(P, K, int(span_bytes))
+    arena = torch.empty(lay.arena_floats, device=dev, dtype=torch.float32)
+    S = lay.worker_stride
+    views = [torch.as_strided(arena, (K, Pp), (S, 1), o) for o in (0, lay.omega_offset, lay.delta_offset)]
     return views + [S]
 
 

@@ -116,6 +116,24 @@ def test_paper_shaped_partition_has_16_components():
     assert (pl.info.K, pl.info.p, pl.info.q) == (16, 3, 2)         # Section 3.3, 16 GPUs
 
 
+def test_recommended_layout_interleaves_rows_over_the_requested_span():
+    P, K = 278626775, 16
+    lay = B.recommend_layout(P, K, 150 * 10**9)
+    row = (P + 63) // 64 * 64
+    assert lay.omega_offset == row and lay.delta_offset == 2 * row
+    assert lay.worker_stride % 1024 == 0 and lay.worker_stride >= 3 * row
+    assert lay.arena_floats == (K - 1) * lay.worker_stride + 3 * row
+    assert 0.99 * 150e9 < 4 * lay.arena_floats <= 150e9
+    dense = B.recommend_layout(P, K, 0)
+    assert dense.worker_stride == 3 * row
+    one = B.recommend_layout(10, 1, 10**9)
+    assert one.arena_floats == 3 * 64
+    with pytest.raises(B.GbmufError):
+        B.recommend_layout(-1, 4, 0)
+    with pytest.raises(B.GbmufError):
+        B.recommend_layout(10, 0, 0)
+
+
 def test_empty_models_make_empty_plans():
     pl = B.Plan([0], K=4, q=1)
     assert pl.info.m == 0 and pl.info.n_tiles == 0 and pl.neighbours_host(0).size == 0
