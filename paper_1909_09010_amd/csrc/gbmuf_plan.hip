@@ -246,8 +246,9 @@ int gbmuf_plan(gbmuf_plan_t **out, const int64_t *comp_offsets, int32_t m, int32
             pl->cand.resize(static_cast<size_t>(K) * pl->C);
             for (int32_t w = 0; w < K; ++w) {
                 ring_of(w, K, pl->p, ring);
-                std::memcpy(pl->cand.data() + static_cast<size_t>(w) * pl->C, ring.data(),
-                            sizeof(int32_t) * static_cast<size_t>(pl->C));
+                if (pl->C > 0)
+                    std::memcpy(pl->cand.data() + static_cast<size_t>(w) * pl->C, ring.data(),
+                                sizeof(int32_t) * static_cast<size_t>(pl->C));
             }
             pl->variant = choose_variant(K);
             if (const char *f = std::getenv("GBMUF_FLAGS")) pl->flags = std::atoi(f) & 3;
