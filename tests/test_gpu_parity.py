@@ -144,6 +144,8 @@ SHAPES = [
     (1, 0, 0, [0, 100, 5000], 0, 0, 3),                            # a single worker
     (2, 0, 1, [0, 3, 50000], 0, 0, 3),
     (100, 0, 7, [0, 1000, 7001], 0, 0, 2),                         # tile narrower than a wavefront
+    (1024, 0, 5, [0, 300, 1501], 0, 0, 2),                         # the largest K: 4 columns per tile
+    (257, 0, 4, [0, 64, 2049], 0, 0, 2),
 ]
 
 
@@ -177,6 +179,62 @@ def test_sync_matches_oracle(K, p, q, off, pad, shift, rounds, mode):
     exact, total = _compare(dev, host, P, f"K={K} q={q} mode={mode}")
     assert exact == total, f"{total - exact} of {total} elements differ in the last bits"
     pl.destroy()
+
+
+def test_denormals_signed_zeros_and_non_finite_values_propagate_like_the_oracle():
+    # fp32 denormals are kept (no flush to zero), -0.0 keeps its sign where IEEE says so,
+    # inf/nan propagate: compared bit for bit except for the payload of NaNs
+    _need_gpu()
+    K, q, off = 8, 2, np.array([0, 1000, 4100], dtype=np.int64)
+    P, stride = 4100, 4160
+    rng = np.random.default_rng(5)
+    base = rng.normal(0, 2e-39, size=(3, K, stride)).astype(np.float32)         # denormal
+    base[:, :, 10:20] = 0.0
+    base[0, :, 20:30] = -0.0
+    base[0, 3, 40] = np.inf
+    base[0, 5, 41] = -np.inf
+    base[1, 2, 42] = np.nan
+    base[2, 1, 43] = np.float32(3e38)
+    base[0, :, 50:60] = np.float32(3e38)                                          # the sum overflows
+    assert (np.abs(base[0, :, 100:200]) < np.finfo(np.float32).tiny).mean() > 0.99
+    pl = B.Plan(off, K, q, 0, seed=3)
+    dev = [torch.from_numpy(b.copy()).to(DEV) for b in base]
+    host = [b.copy() for b in base]
+    for r in range(3):
+        pl.sync(*dev, stride, 0.9, 1.0, 1, r, None)
+        with np.errstate(all="ignore"):
+            oracle.sync(off, K, pl.info.p, q, 3, r, *host, np.float32(0.9), np.float32(1.0), 1)
+    torch.cuda.synchronize()
+    for name, d, h in zip(("theta", "omega", "delta"), dev, host):
+        got = d.cpu().numpy()
+        nan = np.isnan(h)
+        assert (np.isnan(got) == nan).all(), name
+        assert (got.view(np.int32)[~nan] == h.view(np.int32)[~nan]).all(), name
+    assert np.isnan(host[0]).any() and np.isinf(host[0]).any()
+    assert ((np.abs(host[1]) < np.finfo(np.float32).tiny) & (host[1] != 0)).any()   # denormals survived
+    pl.destroy()
+
+
+def test_two_plans_on_two_streams_do_not_disturb_each_other():
+    _need_gpu()
+    K, q, off = 16, 3, np.array([0, 50000, 300000], dtype=np.int64)
+    P = stride = 300000
+    plans = [B.Plan(off, K, q, 0, seed=s) for s in (1, 2)]
+    states = [list(_random_state(K, P, stride, 10 + i)) for i in range(2)]
+    hosts = [_to_host(*st) for st in states]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for r in range(4):
+        for pl, st, s in zip(plans, states, streams):
+            pl.sync(*st, stride, 0.9, 1.0, 1, r, s)
+    for s in streams:
+        s.synchronize()
+    for i, (pl, h) in enumerate(zip(plans, hosts)):
+        for r in range(4):
+            oracle.sync(off, K, pl.info.p, q, i + 1, r, *h, np.float32(0.9), np.float32(1.0), 1)
+        exact, total = _compare(states[i], h, P, f"plan {i}")
+        assert exact == total
+        pl.destroy()
 
 
 def test_sync_equals_sync_table_with_the_sampled_table():
