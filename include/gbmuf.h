@@ -134,9 +134,10 @@ int gbmuf_neighbours_device(const gbmuf_plan_t *plan, uint64_t round, int32_t *o
  * Every average uses the workers' values from before the call (snapshot semantics), the
  * sum runs over the worker and its neighbours in ascending worker id and is multiplied by
  * the rounded constant 1/(q+1).  The three buffers must not overlap.  The call enqueues
- * two kernels on `stream` and returns; it allocates nothing.  Two syncs on the same plan
- * must not run concurrently on different streams (they share the plan's neighbour
- * scratch).  Errors: EINVAL (NULLs, worker_stride < P, unknown mode), EDEVICE.
+ * one or two kernels on `stream` and returns; it allocates nothing.  Two syncs on the same
+ * plan must not run concurrently on different streams (large plans draw the neighbour table
+ * into the plan's scratch with a separate kernel; small, launch-bound plans draw it inside
+ * the fused kernel and use no scratch).  Errors: EINVAL (NULLs, worker_stride < P, unknown mode), EDEVICE.
  */
 int gbmuf_sync(const gbmuf_plan_t *plan, float *replicas, float *global, float *delta,
                int64_t worker_stride, float eta, float zeta, int32_t nesterov,

@@ -43,9 +43,14 @@ class Layout(ctypes.Structure):
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
-        raise ImportError(
-            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
-            "or python -m paper_1909_09010_amd.build).  There is no fallback path.")
+        # nothing built yet: build once with hipcc; there is no other (CPU, eager) path to fall back to
+        try:
+            from .build import build_library
+            build_library(verbose=False)
+        except Exception as e:  # noqa: BLE001
+            raise ImportError(
+                f"{LIB_PATH} is missing and could not be built ({e!r}): run "
+                "python -c 'import __graft_entry__ as g; g.build()'.  There is no fallback path.") from e
     L = ctypes.CDLL(LIB_PATH)
     i32, i64, u64, f32, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_float, ctypes.c_void_p
     L.gbmuf_plan.argtypes = [ctypes.POINTER(vp), vp, i32, i32, i32, i32, u64]

@@ -29,6 +29,11 @@ struct SyncArgs {
     int32_t mode;            // GBMUF_MODE_*
     float eta, zeta, inv;    // inv = 1/(q+1), rounded once on the host
     int32_t flags;           // bit 0: streaming (nontemporal) stores, bit 1: streaming loads
+    // nbr == nullptr: the workgroup draws its component's neighbour rows itself (same bits as
+    // the sampler kernel) from the candidates and the key below; C ints per worker go to LDS
+    const int32_t *cand;     // [K][C], device
+    int32_t C;
+    uint32_t key0, key1, round0, round1;
     const int32_t *periods;  // per-component sync period H_i, or nullptr: every component syncs
     uint64_t step;           // with periods: component i syncs iff step % H_i == 0
 };
@@ -114,7 +119,7 @@ int launch_final_average(const float *theta, int64_t stride, int K, int64_t P, f
                          hipStream_t stream);
 int launch_copy_probe(float *dst, const float *src, int64_t n_floats, int flags, int blocks, hipStream_t stream);
 int launch_sync(const Variant &v, bool vec4, const SyncArgs &a, int64_t n_tiles, hipStream_t stream);
-int prepare_kernels(const Variant &v, int K, int q, size_t *lds_bytes_out);
+int prepare_kernels(const Variant &v, int K, int q, int C, bool *inline_sampling_out);
 const Variant *variant_table(int *count);
 
 }  // namespace gbmuf

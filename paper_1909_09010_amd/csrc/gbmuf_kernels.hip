@@ -87,6 +87,37 @@ __device__ __forceinline__ void stage_ids(uint16_t *ids, const int32_t *nbr, int
     }
 }
 
+// The same rows drawn by the workgroup itself (a.nbr == nullptr): thread w copies worker w's
+// candidates into its LDS row, runs the sampler core and merges itself in.  Saves the
+// separate sampler launch and the neighbour scratch; overlaps with the tile's loads in flight.
+struct LdsRow {
+    int32_t *base;
+    __device__ int32_t &operator()(int32_t x) const { return base[x]; }
+};
+
+__device__ __forceinline__ void draw_ids(uint16_t *ids, int32_t *perm, const SyncArgs &a, int comp, int tid,
+                                         int nthreads)
+{
+    const int K = a.K, q = a.q, C = a.C;
+    for (int w = tid; w < K; w += nthreads) {
+        int32_t *mine = perm + w * C;
+        const int32_t *cand = a.cand + static_cast<int64_t>(w) * C;
+        for (int x = 0; x < C; ++x) mine[x] = cand[x];
+        draw_neighbours(LdsRow{mine}, C, q, a.key0, a.key1, a.round0, a.round1, static_cast<uint32_t>(comp),
+                        static_cast<uint32_t>(w));
+        uint16_t *dst = ids + w * (q + 1);                 // mine[0..q) ascending; insert w
+        int j = 0, o = 0;
+        while (j < q && mine[j] < w) dst[o++] = static_cast<uint16_t>(mine[j++]);
+        dst[o++] = static_cast<uint16_t>(w);
+        while (j < q) dst[o++] = static_cast<uint16_t>(mine[j++]);
+    }
+}
+
+__device__ __forceinline__ size_t ids_words(int K, int q)      // uint16 entries, padded to 16 bytes
+{
+    return (static_cast<size_t>(K) * static_cast<size_t>(q + 1) + 7) & ~static_cast<size_t>(7);
+}
+
 // ---------------------------------------------------------------------------------------
 // 16-byte path: worker rows are 16-byte aligned (bases and stride), a column is 4 floats.
 // Q1 = q+1 when known at compile time (the sum is then fully unrolled), 0 = run-time q.
@@ -160,7 +191,8 @@ __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
         }
     }
 
-    stage_ids(ids, a.nbr, td.comp, K, q, tid, NT);
+    if (a.nbr != nullptr) stage_ids(ids, a.nbr, td.comp, K, q, tid, NT);
+    else draw_ids(ids, reinterpret_cast<int32_t *>(ids + ids_words(K, q)), a, td.comp, tid, NT);
 
 #pragma unroll
     for (int n = 0; n < SLOTS; ++n) tile[tid + n * NT] = th[n];
@@ -277,7 +309,8 @@ __global__ __launch_bounds__(NT) void sync_vec1_kernel(SyncArgs a)
     const int mode = a.mode;
     const int64_t hi = td.lo + td.n;
 
-    stage_ids(ids, a.nbr, td.comp, K, q, tid, NT);
+    if (a.nbr != nullptr) stage_ids(ids, a.nbr, td.comp, K, q, tid, NT);
+    else draw_ids(ids, reinterpret_cast<int32_t *>(ids + ids_words(K, q)), a, td.comp, tid, NT);
 
     for (int64_t first = td.lo; first < hi; first += T) {
         const int ncols = static_cast<int>(hi - first < T ? hi - first : T);
@@ -364,6 +397,11 @@ size_t ids_bytes(int K, int q)
     return (static_cast<size_t>(K) * static_cast<size_t>(q + 1) * sizeof(uint16_t) + 15) & ~static_cast<size_t>(15);
 }
 
+size_t perm_bytes(int K, int C) { return static_cast<size_t>(K) * static_cast<size_t>(C) * sizeof(int32_t); }
+
+// Workgroups draw their own neighbour rows when the candidates of all workers fit 8 KB of LDS.
+bool can_sample_inline(int K, int C) { return perm_bytes(K, C) <= 8192; }
+
 }  // namespace
 
 const Variant *variant_table(int *count)
@@ -374,11 +412,13 @@ const Variant *variant_table(int *count)
 
 // Raises the dynamic-LDS limit of the kernels this plan will launch and reports the LDS
 // bytes one workgroup uses (16-byte path).  GBMUF_EUNSUPPORTED if that exceeds the device.
-int prepare_kernels(const Variant &v, int K, int q, size_t *lds_bytes_out)
+int prepare_kernels(const Variant &v, int K, int q, int C, bool *inline_sampling_out)
 {
-    const size_t lds4 = static_cast<size_t>(v.threads) * v.slots * sizeof(float4) + ids_bytes(K, q);
-    const size_t lds1 = static_cast<size_t>(v.threads) * v.slots * sizeof(float) + ids_bytes(K, q);
-    *lds_bytes_out = lds4;
+    const bool inl = can_sample_inline(K, C);
+    *inline_sampling_out = inl;
+    const size_t extra = ids_bytes(K, q) + (inl ? perm_bytes(K, C) : 0);
+    const size_t lds4 = static_cast<size_t>(v.threads) * v.slots * sizeof(float4) + extra;
+    const size_t lds1 = static_cast<size_t>(v.threads) * v.slots * sizeof(float) + extra;
     int dev = 0, max_lds = 0;
     hipError_t err = hipGetDevice(&dev);
     if (err != hipSuccess) return hip_failed("hipGetDevice", err, GBMUF_EDEVICE);
@@ -403,7 +443,8 @@ int launch_sync(const Variant &v, bool vec4, const SyncArgs &a, int64_t n_tiles,
     KernelFn k = pick_kernel(v, vec4, a.q + 1);
     if (!k) return GBMUF_EINVAL;
     const size_t lds = static_cast<size_t>(v.threads) * v.slots * (vec4 ? sizeof(float4) : sizeof(float)) +
-                       ids_bytes(a.K, a.q);
+                       ids_bytes(a.K, a.q) + (a.nbr == nullptr ? perm_bytes(a.K, a.C) : 0);
+    if (a.nbr == nullptr && (!can_sample_inline(a.K, a.C) || (a.cand == nullptr && a.C > 0))) return GBMUF_EINVAL;
     SyncArgs args = a;
     void *argv[] = {&args};
     // the launch's own status: an earlier, unrelated error of the process is not ours to report

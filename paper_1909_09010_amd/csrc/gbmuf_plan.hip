@@ -25,6 +25,7 @@ struct gbmuf_plan_s {
     int32_t logT = 0;
     float inv = 1.0f;                // 1/(q+1), rounded once
     int32_t flags = 0;               // load/store cache hints of the fused kernel
+    bool inline_sampling = false;    // workgroups draw their own neighbour rows (no sampler launch)
 
     bool has_device = false;
     int device = -1;
@@ -148,8 +149,16 @@ int make_device_state(gbmuf_plan_s &pl)
     }
     err = hipGetDevice(&pl.device);
     if (err != hipSuccess) return hip_failed("hipGetDevice", err, GBMUF_EDEVICE);
-    size_t lds = 0;
-    int rc = prepare_kernels(pl.variant, pl.K, pl.q, &lds);
+    int rc = prepare_kernels(pl.variant, pl.K, pl.q, pl.C, &pl.inline_sampling);
+    // Drawing the rows inside every workgroup saves the sampler launch (about 2 us of a 8 us
+    // sync on a 200k-parameter model) but costs about 2 % once there are millions of tiles:
+    // only launch-bound plans do it.  GBMUF_TWO_KERNELS / GBMUF_ONE_KERNEL force either way.
+    if (pl.tiles.size() > 8192 || std::getenv("GBMUF_TWO_KERNELS")) pl.inline_sampling = false;
+    if (std::getenv("GBMUF_ONE_KERNEL")) {
+        bool can = false;
+        rc = prepare_kernels(pl.variant, pl.K, pl.q, pl.C, &can);
+        pl.inline_sampling = can;
+    }
     if (rc != GBMUF_OK) return rc;
     if ((rc = upload(&pl.d_cand, pl.cand)) != GBMUF_OK) return rc;
     if ((rc = upload(&pl.d_tiles, pl.tiles)) != GBMUF_OK) return rc;
@@ -172,11 +181,16 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int enqueue_sync(const gbmuf_plan_s *pl, const int32_t *nbr_dev, float *theta, float *omega, float *delta,
                  int64_t stride, float eta, float zeta, int32_t mode, hipStream_t stream,
-                 int64_t first_tile = 0, int64_t n_tiles = -1, bool check_periods = false, uint64_t step = 0)
+                 int64_t first_tile = 0, int64_t n_tiles = -1, bool check_periods = false, uint64_t step = 0,
+                 uint64_t round = 0)
 {
     if (n_tiles < 0) n_tiles = static_cast<int64_t>(pl->tiles.size());
     SyncArgs a{};
     a.tiles = pl->d_tiles + first_tile;
+    a.cand = pl->d_cand;                                    // used only when nbr_dev == nullptr
+    a.C = pl->C;
+    a.key0 = static_cast<uint32_t>(pl->seed); a.key1 = static_cast<uint32_t>(pl->seed >> 32);
+    a.round0 = static_cast<uint32_t>(round); a.round1 = static_cast<uint32_t>(round >> 32);
     a.periods = check_periods ? pl->d_periods : nullptr;
     a.step = step;
     a.nbr = nbr_dev;
@@ -190,6 +204,17 @@ int enqueue_sync(const gbmuf_plan_s *pl, const int32_t *nbr_dev, float *theta, f
     return launch_sync(pl->variant, vec4, a, n_tiles, stream);
 }
 
+// Device calls need the plan's GPU to be the current one: its tables live there.
+int check_device(const gbmuf_plan_s *pl)
+{
+    if (!pl->has_device) return GBMUF_EDEVICE;
+    int dev = -1;
+    const hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return hip_failed("hipGetDevice", err, GBMUF_EDEVICE);
+    if (dev != pl->device) return hip_failed("current device is not the plan's device", hipErrorInvalidDevice, GBMUF_EDEVICE);
+    return GBMUF_OK;
+}
+
 int check_sync(const gbmuf_plan_s *pl, const float *theta, const float *omega, const float *delta,
                int64_t stride, int32_t mode)
 {
@@ -197,8 +222,7 @@ int check_sync(const gbmuf_plan_s *pl, const float *theta, const float *omega, c
     if (mode < GBMUF_MODE_NO_RESTART || mode > GBMUF_MODE_GOSSIP_MA) return GBMUF_EINVAL;
     if (mode != GBMUF_MODE_GOSSIP_MA && (!omega || !delta)) return GBMUF_EINVAL;
     if (stride < pl->P) return GBMUF_EINVAL;
-    if (!pl->has_device) return GBMUF_EDEVICE;
-    return GBMUF_OK;
+    return check_device(pl);
 }
 
 SampleArgs sample_args(const gbmuf_plan_s *pl, uint64_t round, int32_t *out)
@@ -335,7 +359,8 @@ int gbmuf_neighbours_host(const gbmuf_plan_t *plan, uint64_t round, int32_t *out
 int gbmuf_neighbours_device(const gbmuf_plan_t *plan, uint64_t round, int32_t *out_dev, void *stream)
 {
     if (!plan) return GBMUF_EINVAL;
-    if (!plan->has_device) return GBMUF_EDEVICE;
+    const int rc = check_device(plan);
+    if (rc != GBMUF_OK) return rc;
     if (plan->q == 0 || plan->m == 0) return GBMUF_OK;
     if (!out_dev) return GBMUF_EINVAL;
     return launch_sampler(sample_args(plan, round, out_dev), static_cast<hipStream_t>(stream));
@@ -347,6 +372,9 @@ int gbmuf_sync(const gbmuf_plan_t *plan, float *replicas, float *global, float *
     int rc = check_sync(plan, replicas, global, delta, worker_stride, nesterov);
     if (rc != GBMUF_OK) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->inline_sampling)
+        return enqueue_sync(plan, nullptr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s, 0, -1, false,
+                            0, round);
     rc = launch_sampler(sample_args(plan, round, plan->d_nbr), s);
     if (rc != GBMUF_OK) return rc;
     return enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s);
@@ -405,14 +433,18 @@ int gbmuf_sync_step(const gbmuf_plan_t *plan, float *replicas, float *global, fl
         }
     }
     if (!any) return GBMUF_OK;
-    rc = launch_sampler(sample_args(plan, step, plan->d_nbr), s);
-    if (rc != GBMUF_OK) return rc;
+    const int32_t *nbr = nullptr;                           // nullptr: workgroups draw their own rows
+    if (!plan->inline_sampling) {
+        rc = launch_sampler(sample_args(plan, step, plan->d_nbr), s);
+        if (rc != GBMUF_OK) return rc;
+        nbr = plan->d_nbr;
+    }
     if (too_many)                                           // scattered schedule: one launch, checked on the device
-        return enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s, 0, -1,
-                            true, step);
+        return enqueue_sync(plan, nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s, 0, -1, true,
+                            step, step);
     for (int r = 0; r < n_runs; ++r) {
-        rc = enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s,
-                          runs[r].first, runs[r].count);
+        rc = enqueue_sync(plan, nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s, runs[r].first,
+                          runs[r].count, false, 0, step);
         if (rc != GBMUF_OK) return rc;
     }
     return GBMUF_OK;
@@ -422,7 +454,8 @@ int gbmuf_final_average(const gbmuf_plan_t *plan, const float *replicas, int64_t
                         void *stream)
 {
     if (!plan || !replicas || !out_dev || worker_stride < plan->P) return GBMUF_EINVAL;
-    if (!plan->has_device) return GBMUF_EDEVICE;
+    const int rc = check_device(plan);
+    if (rc != GBMUF_OK) return rc;
     return launch_final_average(replicas, worker_stride, plan->K, plan->P, 1.0f / static_cast<float>(plan->K), out_dev,
                                 static_cast<hipStream_t>(stream));
 }

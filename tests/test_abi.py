@@ -134,6 +134,13 @@ def test_recommended_layout_interleaves_rows_over_the_requested_span():
         B.recommend_layout(10, 0, 0)
 
 
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
 def test_empty_models_make_empty_plans():
     pl = B.Plan([0], K=4, q=1)
     assert pl.info.m == 0 and pl.info.n_tiles == 0 and pl.neighbours_host(0).size == 0

@@ -237,6 +237,34 @@ def test_two_plans_on_two_streams_do_not_disturb_each_other():
         pl.destroy()
 
 
+@pytest.mark.parametrize("K,q,P", [(16, 3, 150000), (16, 3, 3000001), (64, 4, 70001), (4, 1, 195048), (8, 2, 2500000)])
+def test_in_kernel_sampling_and_the_sampler_kernel_give_identical_results(K, q, P, monkeypatch):
+    # small plans draw the neighbour rows inside the fused kernel, large ones launch the sampler
+    # first; both ways (forced through the tuning switches read at plan creation) must agree bitwise
+    _need_gpu()
+    off = np.array([0, P // 3, P // 3 + 1, P], dtype=np.int64)
+    stride = (P + 63) // 64 * 64
+    results = []
+    for switch in ("GBMUF_ONE_KERNEL", "GBMUF_TWO_KERNELS"):
+        monkeypatch.delenv("GBMUF_ONE_KERNEL", raising=False)
+        monkeypatch.delenv("GBMUF_TWO_KERNELS", raising=False)
+        monkeypatch.setenv(switch, "1")
+        pl = B.Plan(off, K, q, 0, seed=21)
+        st = list(_random_state(K, P, stride, 9))
+        for r in range(3):
+            pl.sync(*st, stride, 0.9, 1.0, 1, r, None)
+        torch.cuda.synchronize()
+        results.append(st)
+        pl.destroy()
+    for x, y in zip(*results):
+        assert torch.equal(x, y)
+    host = _to_host(*_random_state(K, P, stride, 9))
+    for r in range(3):
+        oracle.sync(off, K, oracle.default_p(K), q, 21, r, *host, np.float32(0.9), np.float32(1.0), 1)
+    exact, total = _compare(results[0], host, P, "in-kernel sampling")
+    assert exact == total
+
+
 def test_sync_equals_sync_table_with_the_sampled_table():
     _need_gpu()
     K, q, off = 16, 3, np.array([0, 1000, 66000], dtype=np.int64)
