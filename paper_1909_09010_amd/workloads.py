@@ -41,7 +41,7 @@ class Workload:
     kind: str = "lstm_lm"       # "lstm_lm": plain LSTM LM with full softmax; "paper": Section 3.2's model
 
 
-# The five benchmark configurations (index = position in BASELINE.json's list) and "4b",
+# The five benchmark configurations (index = position in the benchmark's list) and "4b",
 # the 4-layer variant whose size matches the "~135M params / ~104 GB" that config 4 states.
 WORKLOADS = {
     "tiny": Workload("tiny", 4, 1, 1000, 64, 64, 2, None, 0.9, 1.0, 1, 10, "normal", 0.05, 0.01, 0.0, 0),

@@ -424,12 +424,17 @@ def test_config2_large_vocab_unpadded_stride_takes_the_4_byte_path():
 
 def test_config3_chunked_sampled_columns():
     _need_gpu()
-    _run_sampled(W.get(3))
+    _run_sampled(W.get(3), spread=True)
+
+
+def test_config3_chunked_contiguous_layout():
+    _need_gpu()
+    _run_sampled(W.get(3), rounds=3)
 
 
 def test_config4_k64_sampled_columns():
     _need_gpu()
-    _run_sampled(W.get(4))
+    _run_sampled(W.get(4), spread=True)
 
 
 def test_config4b_k64_4layer_sampled_columns():
