@@ -242,6 +242,9 @@ def main() -> int:
                            "effective_GBps": BYTES_PER_WORKER_PARAM * v / 1e9, "kernel_GBps": kb,
                            "kernel_frac": kb / HBM_PEAK_GBPS})
         out["other_workloads"] = others
+        gc = run_gpu(w, min(args.steps, 5), args.warmup, contiguous=True)      # the same workload, rows side by side
+        out["contiguous_layout"] = {"kernel_ms": gc["kernel_ms"],
+                                    "kernel_frac": BYTES_PER_WORKER_PARAM * wp / (gc["kernel_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     if args.calibrate:
         out["copy_probe"] = run_copy_probe()
     if not args.no_cpu:

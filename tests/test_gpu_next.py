@@ -155,3 +155,60 @@ def test_gossip_ma_at_benchmark_size():
     torch.cuda.synchronize()
     assert (theta.index_select(1, idx).cpu().numpy() == host).all()
     pl.destroy()
+
+
+def test_full_size_every_element_all_neighbours_is_the_global_mean():
+    # q = K-1 (every other worker): Section 2.2's degenerate case without gossip.  Every worker's
+    # average is then the same ascending-id sum over all workers times fl(1/K), which plain
+    # elementwise torch ops reproduce operation for operation: checked on EVERY element of the
+    # large-vocabulary model, in the benchmark's HBM-spanning layout.
+    _need_gpu()
+    w = W.get(2)
+    off = W.component_offsets(w)
+    P = int(off[-1])
+    span = W.default_span_bytes(DEV, 3 * w.K * W.padded_stride(P) * 4)
+    theta, _, _, stride = W.alloc_state(w.K, P, DEV, span_bytes=span)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(11)
+    for k in range(w.K):
+        theta[k].normal_(0, 0.02, generator=g)
+    s = theta[0].clone()
+    for k in range(1, w.K):
+        s += theta[k]                                       # one rounded fp32 add per worker, ascending
+    s *= torch.tensor(1.0, device=DEV) / torch.tensor(float(w.K), device=DEV)
+    pl = B.Plan(off, w.K, w.K - 1, -1, seed=0)
+    pl.sync(theta, None, None, stride, 0.0, 1.0, B.MODE_GOSSIP_MA, 0, None)
+    torch.cuda.synchronize()
+    for k in range(w.K):
+        assert torch.equal(theta[k, :P], s[:P]), f"worker {k}"
+    pl.destroy()
+
+
+def test_full_size_every_element_invariants_of_one_sync():
+    # Properties that hold at any size, checked on every element of config 3 (2,127 components):
+    # the neighbour average lies between the workers' min and max; omega' = omega + Delta';
+    # theta' = omega' + eta*Delta' (the restart statement), the latter two bit for bit.
+    _need_gpu()
+    w = W.get(3)
+    off = W.component_offsets(w)
+    P = int(off[-1])
+    theta, omega, delta = W.init_state(w, DEV)
+    stride = theta.stride(0)
+    lo, hi = theta.min(dim=0).values, theta.max(dim=0).values
+    omega_before = omega.clone()
+    avg = theta.clone()
+    pl = B.Plan(off, w.K, w.q, w.p, seed=w.seed)
+    pl.sync(avg, None, None, stride, 0.0, 1.0, B.MODE_GOSSIP_MA, 0, None)
+    slack = 4 * torch.finfo(torch.float32).eps * torch.maximum(lo.abs(), hi.abs())
+    assert bool(((avg >= lo - slack) & (avg <= hi + slack))[:, :P].all())
+    assert float((avg - theta)[:, :P].abs().max()) > 1e-3                   # and it did average
+    del lo, hi, slack
+    eta = 0.9
+    pl.sync(theta, omega, delta, stride, eta, w.zeta, B.MODE_PAPER, 0, None)
+    torch.cuda.synchronize()
+    assert torch.equal(omega[:, :P], (omega_before + delta)[:, :P])
+    step = delta * torch.tensor(eta, dtype=torch.float32, device=DEV)       # rounded product, then rounded add
+    assert torch.equal(theta[:, :P], (omega + step)[:, :P])
+    # zeta = 1: omega' equals the average up to the rounding of three additions
+    assert float((omega - avg)[:, :P].abs().max()) < 1e-6
+    pl.destroy()
