@@ -186,3 +186,46 @@ def test_keying_matches_the_documented_counter_layout():
             cand = oracle.ring_candidates(w, K, p)
             want = cand[(int(u[0]) * len(cand)) >> 32]
             assert oracle.sample(K, p, 1, seed, rnd, w, i).tolist() == [want]
+
+
+def test_all_subsets_are_equally_likely():
+    # K = 16, p = 3, q = 3: C(6,3) = 20 subsets of the 6 ring neighbours, each with probability 1/20
+    K, p, q, m = 16, 3, 3, 2500
+    pos = _position_of(K, p)
+    counts = {}
+    n = 0
+    for rnd in range(3):
+        t = oracle.neighbour_table(m, K, p, q, seed=99, round=rnd)
+        for w in range(K):
+            lut = np.full(K, -1)
+            for v, j in pos[w].items():
+                lut[v] = j
+            rows = np.sort(lut[t[:, w, :]], axis=1)
+            keys = rows[:, 0] * 36 + rows[:, 1] * 6 + rows[:, 2]
+            for k, c in zip(*np.unique(keys, return_counts=True)):
+                counts[int(k)] = counts.get(int(k), 0) + int(c)
+            n += m
+    assert len(counts) == 20
+    exp = n / 20
+    chi2 = sum((c - exp) ** 2 / exp for c in counts.values())
+    assert chi2 < 60.0, chi2                      # 19 dof: P(chi2 > 60) ~ 4e-6
+
+
+def test_later_draws_use_the_next_counter_block():
+    # spec conformance (not a pin): draws 4..7 take the words of the block whose last counter
+    # word is worker + 65536; the whole partial shuffle replayed with Python integers
+    K, p, q = 33, 7, 9
+    seed, rnd = 0xFEDCBA9876543210, 5
+    for w in (0, 16, 32):
+        for i in (0, 7):
+            cand = oracle.ring_candidates(w, K, p).tolist()
+            C = len(cand)
+            assert C == 14
+            words = []
+            for blk in range(3):
+                words += [int(x) for x in oracle.philox4x32_10([rnd & 0xFFFFFFFF, rnd >> 32, i, w + 65536 * blk],
+                                                               [seed & 0xFFFFFFFF, seed >> 32])]
+            for j in range(q):
+                r = j + ((words[j] * (C - j)) >> 32)
+                cand[j], cand[r] = cand[r], cand[j]
+            assert oracle.sample(K, p, q, seed, rnd, w, i).tolist() == sorted(cand[:q])
