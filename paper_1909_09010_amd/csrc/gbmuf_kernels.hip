@@ -67,6 +67,19 @@ __device__ __forceinline__ void filter(float avg, float om, float de, float eta,
     th_out = tn; om_out = on; de_out = dn;
 }
 
+// Which tile this workgroup takes.  Normally its own index.  With flag bit 3 (set on odd rounds
+// of mid-sized states) the list is walked backwards, so that what the previous sync wrote last
+// is read first, while it is still in the 256 MB memory-side cache; the reversal keeps the
+// index modulo 8, i.e. the XCD (workgroups are dealt round-robin to the 8 XCDs) and its L2.
+__device__ __forceinline__ unsigned tile_of_block(int flags)
+{
+    const unsigned b = blockIdx.x;
+    if (!(flags & 8)) return b;
+    const unsigned r = b & 7u;
+    const unsigned in_class = (gridDim.x - r + 7u) >> 3;      // tiles with index == r (mod 8)
+    return ((in_class - 1u - (b >> 3)) << 3) | r;
+}
+
 // Neighbour rows of this tile's component -> LDS, merged with the worker itself and sorted
 // ascending: ids[w][0..q].  Ids are clamped into [0, K) so that a bad caller table cannot
 // index outside the tile.
@@ -146,7 +159,7 @@ __global__ __launch_bounds__(NT) void sync_vec4_kernel(SyncArgs a)
     uint16_t *ids = reinterpret_cast<uint16_t *>(lds4 + NT * SLOTS);
 
     const int tid = threadIdx.x;
-    const TileDesc td = a.tiles[blockIdx.x];
+    const TileDesc td = a.tiles[tile_of_block(a.flags)];
     if (a.periods != nullptr && a.step % static_cast<uint64_t>(a.periods[td.comp]) != 0) return;  // whole workgroup
     const int K = a.K, q = a.q, q1 = (Q1 > 0) ? Q1 : a.q + 1;
     const int logT = a.logT, T = 1 << logT;
@@ -302,7 +315,7 @@ __global__ __launch_bounds__(NT) void sync_vec1_kernel(SyncArgs a)
     uint16_t *ids = reinterpret_cast<uint16_t *>(tile + NT * SLOTS);
 
     const int tid = threadIdx.x;
-    const TileDesc td = a.tiles[blockIdx.x];
+    const TileDesc td = a.tiles[tile_of_block(a.flags)];
     if (a.periods != nullptr && a.step % static_cast<uint64_t>(a.periods[td.comp]) != 0) return;  // whole workgroup
     const int K = a.K, q = a.q, q1 = a.q + 1;
     const int logT = a.logT, T = 1 << logT;

@@ -26,6 +26,7 @@ struct gbmuf_plan_s {
     float inv = 1.0f;                // 1/(q+1), rounded once
     int32_t flags = 0;               // load/store cache hints of the fused kernel
     bool inline_sampling = false;    // workgroups draw their own neighbour rows (no sampler launch)
+    bool alternate = true;           // odd rounds walk the tile list backwards (see tile_of_block)
 
     bool has_device = false;
     int device = -1;
@@ -95,7 +96,7 @@ const Variant &choose_variant(int K)
     return tab[pick];
 }
 
-// Split every component into runs of at most T 16-byte columns.
+// Split every component into runs of at most T 16-byte columns (the fused kernel's work list).
 void build_tiles(gbmuf_plan_s &pl)
 {
     const int64_t T = static_cast<int64_t>(1) << pl.logT;
@@ -106,11 +107,18 @@ void build_tiles(gbmuf_plan_s &pl)
         pl.tile_start[static_cast<size_t>(i)] = static_cast<int64_t>(pl.tiles.size());
         pl.tile_start[static_cast<size_t>(i) + 1] = static_cast<int64_t>(pl.tiles.size());
         if (a >= b) continue;
+        // Tile boundaries sit at multiples of T columns counted from the row start, not from the
+        // component start: with rows aligned to T*16 bytes every interior tile then covers whole
+        // cache lines (a component that starts mid-line only gets a short first tile).  Tiles
+        // that straddle lines cost a quarter of the bandwidth on MI355X.
         const int64_t ga = a >> 2, gb = (b + 3) >> 2;
-        for (int64_t g = ga; g < gb; g += T) {
+        for (int64_t g = ga; g < gb;) {
+            int64_t next = (g / T + 1) * T;
+            if (next > gb) next = gb;
             const int64_t lo = (g << 2) > a ? (g << 2) : a;
-            const int64_t end = ((g + T) << 2) < b ? ((g + T) << 2) : b;
+            const int64_t end = (next << 2) < b ? (next << 2) : b;
             pl.tiles.push_back(TileDesc{lo, static_cast<int32_t>(end - lo), i});
+            g = next;
         }
         pl.tile_start[static_cast<size_t>(i) + 1] = static_cast<int64_t>(pl.tiles.size());
     }
@@ -198,7 +206,7 @@ int enqueue_sync(const gbmuf_plan_s *pl, const int32_t *nbr_dev, float *theta, f
     a.stride = stride;
     a.K = pl->K; a.q = pl->q; a.logT = pl->logT; a.mode = mode;
     a.eta = eta; a.zeta = zeta; a.inv = pl->inv;
-    a.flags = pl->flags;
+    a.flags = pl->flags | ((pl->alternate && (round & 1)) ? 8 : 0);
     bool vec4 = aligned16(theta) && (stride % 4 == 0);
     if (mode != GBMUF_MODE_GOSSIP_MA) vec4 = vec4 && aligned16(omega) && aligned16(delta);
     return launch_sync(pl->variant, vec4, a, n_tiles, stream);
@@ -276,6 +284,7 @@ int gbmuf_plan(gbmuf_plan_t **out, const int64_t *comp_offsets, int32_t m, int32
             }
             pl->variant = choose_variant(K);
             if (const char *f = std::getenv("GBMUF_FLAGS")) pl->flags = std::atoi(f) & 3;
+            pl->alternate = std::getenv("GBMUF_NO_ALTERNATE") == nullptr;   // tuning switch
             const int slots = pl->variant.threads * pl->variant.slots;
             if (K > slots) rc = GBMUF_EUNSUPPORTED;
             int lg = 0;
@@ -377,7 +386,8 @@ int gbmuf_sync(const gbmuf_plan_t *plan, float *replicas, float *global, float *
                             0, round);
     rc = launch_sampler(sample_args(plan, round, plan->d_nbr), s);
     if (rc != GBMUF_OK) return rc;
-    return enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s);
+    return enqueue_sync(plan, plan->d_nbr, replicas, global, delta, worker_stride, eta, zeta, nesterov, s, 0, -1, false,
+                        0, round);
 }
 
 int gbmuf_plan_set_periods(gbmuf_plan_t *plan, const int32_t *periods_host)
@@ -473,7 +483,7 @@ int gbmuf_sync_table(const gbmuf_plan_t *plan, const int32_t *nbr_dev, float *re
 int gbmuf_recommend_layout(int64_t P, int32_t K, int64_t span_bytes, gbmuf_layout_t *out)
 {
     if (!out || P < 0 || K < 1 || span_bytes < 0) return GBMUF_EINVAL;
-    const int64_t row = (P + 63) / 64 * 64;
+    const int64_t row = (P + 1023) / 1024 * 1024;          // rows start on 4 KB: tiles cover whole cache lines
     int64_t stride = 3 * row;
     if (K > 1) {
         const int64_t spread = (span_bytes / 4 - 3 * row) / (K - 1) / 1024 * 1024;

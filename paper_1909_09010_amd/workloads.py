@@ -136,7 +136,7 @@ def n_params(w: Workload) -> int:
     return int(sum(r * c for _, r, c in tensors(w)))
 
 
-def padded_stride(P: int, multiple: int = 64) -> int:
+def padded_stride(P: int, multiple: int = 1024) -> int:
     return (P + multiple - 1) // multiple * multiple
 
 
@@ -144,7 +144,7 @@ def alloc_state(K: int, P: int, device, span_bytes: Optional[int] = None, stride
     """Uninitialised theta, omega, delta as [K, P_padded] float32 views plus their row stride.
 
     span_bytes None: three separate contiguous tensors (row stride = ``stride`` or P rounded
-    up to 64).  span_bytes set: ONE arena in which worker w's three rows sit side by side,
+    up to 1024 floats = 4 KB, so that every row starts on a 4 KB boundary).  span_bytes set: ONE arena in which worker w's three rows sit side by side,
     [theta_w | omega_w | delta_w | gap], with the row stride chosen so that the K rows cover
     about span_bytes of HBM.  On MI355X the sync kernel is measurably faster when the rows it
     streams concurrently are spread over much more than ~70 GB of HBM address space (more

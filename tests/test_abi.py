@@ -48,7 +48,8 @@ def test_plan_resolves_the_papers_defaults(name):
     assert i.p == oracle.default_p(w.K) and i.C == min(2 * i.p, w.K - 1)
     T = i.tile_columns
     assert T & (T - 1) == 0 and w.K * T <= i.threads * 16
-    want_tiles = sum(-(-(((b + 3) >> 2) - (a >> 2)) // T) for a, b in zip(off[:-1], off[1:]) if b > a)
+    # tiles end at multiples of T columns counted from the row start
+    want_tiles = sum(-(-((b + 3) >> 2) // T) - (a >> 2) // T for a, b in zip(off[:-1], off[1:]) if b > a)
     assert i.n_tiles == want_tiles
     for wk in {0, 1, w.K // 2, w.K - 1}:
         assert pl.candidates_host(wk).tolist() == oracle.ring_candidates(wk, w.K, i.p).tolist()
@@ -119,7 +120,7 @@ def test_paper_shaped_partition_has_16_components():
 def test_recommended_layout_interleaves_rows_over_the_requested_span():
     P, K = 278626775, 16
     lay = B.recommend_layout(P, K, 150 * 10**9)
-    row = (P + 63) // 64 * 64
+    row = (P + 1023) // 1024 * 1024
     assert lay.omega_offset == row and lay.delta_offset == 2 * row
     assert lay.worker_stride % 1024 == 0 and lay.worker_stride >= 3 * row
     assert lay.arena_floats == (K - 1) * lay.worker_stride + 3 * row
@@ -127,7 +128,7 @@ def test_recommended_layout_interleaves_rows_over_the_requested_span():
     dense = B.recommend_layout(P, K, 0)
     assert dense.worker_stride == 3 * row
     one = B.recommend_layout(10, 1, 10**9)
-    assert one.arena_floats == 3 * 64
+    assert one.arena_floats == 3 * 1024
     with pytest.raises(B.GbmufError):
         B.recommend_layout(-1, 4, 0)
     with pytest.raises(B.GbmufError):
