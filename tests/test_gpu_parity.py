@@ -304,6 +304,18 @@ def test_rounds_are_stateless_resume_is_bit_identical_on_a_side_stream():
         assert torch.equal(x, y)
 
 
+def test_plain_c_program_on_the_c_abi_matches_the_oracle():
+    # tests/abi_smoke.c: no Python, no torch; device memory from the HIP runtime
+    _need_gpu()
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi_smoke")
+    if not os.path.exists(exe):
+        pytest.skip("tests/abi_smoke has not been built (run __graft_entry__.build())")
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.startswith("abi_smoke ok"), (r.stdout, r.stderr)
+
+
 def test_sync_argument_errors():
     _need_gpu()
     pl = B.Plan([0, 64], K=4, q=1)
