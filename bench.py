@@ -110,6 +110,48 @@ def run_gpu(w, steps: int, warmup: int, contiguous: bool = False):
                 kernel_ms=kernel_ms, finite=finite, layout="contiguous" if span is None else "interleaved_rows")
 
 
+def run_other_entry_points(w, launches: int = 5):
+    """The two further kernels on the same workload: the gossip-MA branch (theta only: 8 B per
+    worker-param) and the final model average (4(K+1) B per parameter)."""
+    import numpy as np
+    import torch
+
+    from paper_1909_09010_amd import binding, workloads
+
+    dev = "cuda:0"
+    off = workloads.component_offsets(w)
+    P = int(off[-1])
+    span = workloads.default_span_bytes(dev, 3 * w.K * workloads.padded_stride(P) * 4)
+    theta, _, _, stride = workloads.alloc_state(w.K, P, dev, span_bytes=span)
+    theta.normal_(0, 0.02)
+    out = torch.empty(P, device=dev)
+    plan = binding.Plan(off, w.K, w.q, w.p, seed=w.seed)
+    stream = torch.cuda.current_stream()
+
+    def timed(fn):
+        fn(0)
+        pairs = []
+        for r in range(1, launches + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn(r)
+            e1.record(stream)
+            pairs.append((e0, e1))
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+
+    ma = timed(lambda r: plan.sync(theta, None, None, stride, 0.0, 1.0, binding.MODE_GOSSIP_MA, r, stream))
+    fa = timed(lambda r: plan.final_average(theta, stride, out, stream))
+    plan.destroy()
+    res = {"gossip_ma": {"ms": ma, "algorithmic_bytes": 8 * w.K * P, "GBps": 8 * w.K * P / ma / 1e6,
+                         "frac": 8 * w.K * P / ma / 1e6 / HBM_PEAK_GBPS, "note": "whole sync: sampler + kernel"},
+           "final_average": {"ms": fa, "algorithmic_bytes": 4 * (w.K + 1) * P, "GBps": 4 * (w.K + 1) * P / fa / 1e6,
+                             "frac": 4 * (w.K + 1) * P / fa / 1e6 / HBM_PEAK_GBPS}}
+    del theta, out
+    torch.cuda.empty_cache()
+    return res
+
+
 def run_copy_probe(n_floats: int = 1 << 28, launches: int = 3):
     """gbmuf_probe_copy on two 1 GiB buffers: 4*n bytes read and 4*n bytes written per launch."""
     import numpy as np
@@ -247,6 +289,7 @@ def main() -> int:
                            "effective_GBps": BYTES_PER_WORKER_PARAM * v / 1e9, "kernel_GBps": kb,
                            "kernel_frac": kb / HBM_PEAK_GBPS})
         out["other_workloads"] = others
+        out["other_entry_points"] = run_other_entry_points(w)
         if gc is not None:
             out["contiguous_layout"] = {"kernel_ms": gc["kernel_ms"],
                                         "kernel_frac": BYTES_PER_WORKER_PARAM * wp / (gc["kernel_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
