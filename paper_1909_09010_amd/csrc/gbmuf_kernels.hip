@@ -431,15 +431,15 @@ const Variant *variant_table(int *count)
     return kVariants;
 }
 
-// Raises the dynamic-LDS limit of the kernels this plan will launch and reports the LDS
-// bytes one workgroup uses (16-byte path).  GBMUF_EUNSUPPORTED if that exceeds the device.
+// Raises the dynamic-LDS limit of the kernels this plan will launch to the device's maximum
+// (so that plans with different needs can share a kernel) and says whether workgroups can
+// draw their own neighbour rows.  GBMUF_EUNSUPPORTED if one workgroup's LDS exceeds the device.
 int prepare_kernels(const Variant &v, int K, int q, int C, bool *inline_sampling_out)
 {
     const bool inl = can_sample_inline(K, C);
     *inline_sampling_out = inl;
     const size_t extra = ids_bytes(K, q) + (inl ? perm_bytes(K, C) : 0);
     const size_t lds4 = static_cast<size_t>(v.threads) * v.slots * sizeof(float4) + extra;
-    const size_t lds1 = static_cast<size_t>(v.threads) * v.slots * sizeof(float) + extra;
     int dev = 0, max_lds = 0;
     hipError_t err = hipGetDevice(&dev);
     if (err != hipSuccess) return hip_failed("hipGetDevice", err, GBMUF_EDEVICE);
@@ -448,11 +448,9 @@ int prepare_kernels(const Variant &v, int K, int q, int C, bool *inline_sampling
     if (lds4 > static_cast<size_t>(max_lds)) return GBMUF_EUNSUPPORTED;
     KernelFn k4 = pick_kernel(v, true, q + 1), k1 = pick_kernel(v, false, q + 1);
     if (!k4 || !k1) return GBMUF_EINVAL;
-    err = hipFuncSetAttribute(reinterpret_cast<const void *>(k4), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              static_cast<int>(lds4));
+    err = hipFuncSetAttribute(reinterpret_cast<const void *>(k4), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
     if (err != hipSuccess) return hip_failed("hipFuncSetAttribute(16-byte kernel)", err, GBMUF_EDEVICE);
-    err = hipFuncSetAttribute(reinterpret_cast<const void *>(k1), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              static_cast<int>(lds1));
+    err = hipFuncSetAttribute(reinterpret_cast<const void *>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
     if (err != hipSuccess) return hip_failed("hipFuncSetAttribute(4-byte kernel)", err, GBMUF_EDEVICE);
     return GBMUF_OK;
 }

@@ -265,6 +265,25 @@ def test_in_kernel_sampling_and_the_sampler_kernel_give_identical_results(K, q, 
     assert exact == total
 
 
+def test_plans_with_different_lds_needs_coexist():
+    # a plan with long neighbour rows (more LDS) made first must keep working after a plan with
+    # short rows has been made for the same kernel
+    _need_gpu()
+    off = np.array([0, 3000, 9001], dtype=np.int64)
+    K, P, stride = 64, 9001, 9216
+    big = B.Plan(off, K, 40, -1, seed=1)             # run-time q kernel, 64*41 ids
+    small = B.Plan(off, K, 8, -1, seed=1)            # same kernel (q+1 > 5), 64*9 ids
+    for pl, q in ((big, 40), (small, 8), (big, 40)):
+        st = list(_random_state(K, P, stride, 3))
+        host = _to_host(*st)
+        pl.sync(*st, stride, 0.9, 1.0, 1, 0, None)
+        oracle.sync(off, K, K // 2, q, 1, 0, *host, np.float32(0.9), np.float32(1.0), 1)
+        exact, total = _compare(st, host, P, f"q={q}")
+        assert exact == total
+    big.destroy()
+    small.destroy()
+
+
 def test_sync_equals_sync_table_with_the_sampled_table():
     _need_gpu()
     K, q, off = 16, 3, np.array([0, 1000, 66000], dtype=np.int64)
