@@ -56,11 +56,16 @@ def lib() -> ctypes.CDLL:
         L.gbmuf_oracle_ring_candidates.restype = i32
         L.gbmuf_oracle_sample.argtypes = [i32, i32, i32, u64, u64, i32, i32, vp]
         L.gbmuf_oracle_neighbour_table.argtypes = [i32, i32, i32, i32, u64, u64, vp]
+        L.gbmuf_oracle_neighbour_table_q.argtypes = [i32, i32, i32, vp, i32, u64, u64, vp]
         for suffix, real in (("f32", ctypes.c_float), ("f64", ctypes.c_double)):
             f = getattr(L, "gbmuf_oracle_sync_table_" + suffix)
             f.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, i64, real, real, i32]
             f = getattr(L, "gbmuf_oracle_sync_" + suffix)
             f.argtypes = [vp, i32, i32, i32, i32, u64, u64, vp, vp, vp, vp, i64, real, real, i32]
+            f = getattr(L, "gbmuf_oracle_sync_table_q_" + suffix)
+            f.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, vp, vp, i64, real, real, i32]
+            f = getattr(L, "gbmuf_oracle_sync_q_" + suffix)
+            f.argtypes = [vp, i32, i32, i32, vp, u64, u64, vp, vp, vp, vp, i64, real, real, i32]
             f = getattr(L, "gbmuf_oracle_final_average_" + suffix)
             f.argtypes = [i32, i64, vp, i64, vp]
         L.gbmuf_oracle_threads.restype = ctypes.c_int
@@ -106,9 +111,19 @@ def sample(K: int, p: int, q: int, seed: int, round: int, w: int, i: int) -> np.
     return out[:q].copy()
 
 
-def neighbour_table(m: int, K: int, p: int, q: int, seed: int, round: int) -> np.ndarray:
-    out = np.zeros((m, K, q), dtype=np.int32)
-    _check(lib().gbmuf_oracle_neighbour_table(m, K, p, q, seed, round, _ptr(out)), "neighbour_table")
+def neighbour_table(m: int, K: int, p: int, q, seed: int, round: int, width=None) -> np.ndarray:
+    """Neighbour table of one sync.  ``q`` an int: ``[m, K, q]``.  ``q`` a sequence of m ints
+    (component i draws q[i] neighbours): ``[m, K, width]`` (width defaults to max q), rows
+    filled with -1 beyond their q[i] entries."""
+    if np.ndim(q) == 0:
+        out = np.zeros((m, K, int(q)), dtype=np.int32)
+        _check(lib().gbmuf_oracle_neighbour_table(m, K, p, int(q), seed, round, _ptr(out)), "neighbour_table")
+        return out
+    qv = np.ascontiguousarray(q, dtype=np.int32)
+    assert qv.shape == (m,)
+    width = int(qv.max(initial=0)) if width is None else int(width)
+    out = np.zeros((m, K, width), dtype=np.int32)
+    _check(lib().gbmuf_oracle_neighbour_table_q(m, K, p, _ptr(qv), width, seed, round, _ptr(out)), "neighbour_table_q")
     return out
 
 
@@ -121,27 +136,42 @@ def _state_args(off, theta, omega, delta):
     return off, suffix, theta.shape[0], theta.shape[1]
 
 
-def sync_table(off, nbr, theta, omega, delta, eta, zeta, mode=MODE_PAPER, active=None) -> None:
-    """One sync with a caller-supplied neighbour table ``[m, K, q]`` (in place)."""
+def sync_table(off, nbr, theta, omega, delta, eta, zeta, mode=MODE_PAPER, active=None, q=None) -> None:
+    """One sync with a caller-supplied neighbour table (in place): ``[m, K, q]``, or, with
+    ``q`` a sequence of m ints, ``[m, K, width]`` of which component i uses q[i] entries."""
     off, suffix, K, stride = _state_args(off, theta, omega, delta)
     m = len(off) - 1
     nbr = np.ascontiguousarray(nbr, dtype=np.int32)
     assert nbr.ndim == 3 and nbr.shape[0] == m and nbr.shape[1] == K
-    q = nbr.shape[2]
     act = None if active is None else np.ascontiguousarray(active, dtype=np.uint8)
     assert act is None or act.shape == (m,)
-    f = getattr(lib(), "gbmuf_oracle_sync_table_" + suffix)
-    _check(f(_ptr(off), m, K, q, _ptr(nbr), _ptr(act), _ptr(theta), _ptr(omega), _ptr(delta),
-             stride, eta, zeta, mode), "sync_table")
+    if q is None:
+        f = getattr(lib(), "gbmuf_oracle_sync_table_" + suffix)
+        _check(f(_ptr(off), m, K, nbr.shape[2], _ptr(nbr), _ptr(act), _ptr(theta), _ptr(omega), _ptr(delta),
+                 stride, eta, zeta, mode), "sync_table")
+        return
+    qv = np.ascontiguousarray(q, dtype=np.int32)
+    assert qv.shape == (m,)
+    f = getattr(lib(), "gbmuf_oracle_sync_table_q_" + suffix)
+    _check(f(_ptr(off), m, K, _ptr(qv), nbr.shape[2], _ptr(nbr), _ptr(act), _ptr(theta), _ptr(omega), _ptr(delta),
+             stride, eta, zeta, mode), "sync_table_q")
 
 
 def sync(off, K, p, q, seed, round, theta, omega, delta, eta, zeta, mode=MODE_PAPER, active=None) -> None:
-    """One sync with neighbours drawn for ``(seed, round)`` (in place)."""
+    """One sync with neighbours drawn for ``(seed, round)`` (in place); ``q`` an int, or a
+    sequence of m ints (component i draws q[i] neighbours)."""
     off, suffix, K2, stride = _state_args(off, theta, omega, delta)
     assert K2 == K
     m = len(off) - 1
     act = None if active is None else np.ascontiguousarray(active, dtype=np.uint8)
     assert act is None or act.shape == (m,)
+    if np.ndim(q) != 0:
+        qv = np.ascontiguousarray(q, dtype=np.int32)
+        assert qv.shape == (m,)
+        f = getattr(lib(), "gbmuf_oracle_sync_q_" + suffix)
+        _check(f(_ptr(off), m, K, p, _ptr(qv), seed, round, _ptr(act), _ptr(theta), _ptr(omega), _ptr(delta),
+                 stride, eta, zeta, mode), "sync_q")
+        return
     f = getattr(lib(), "gbmuf_oracle_sync_" + suffix)
     _check(f(_ptr(off), m, K, p, q, seed, round, _ptr(act), _ptr(theta), _ptr(omega), _ptr(delta),
              stride, eta, zeta, mode), "sync")

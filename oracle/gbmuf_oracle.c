@@ -9,9 +9,11 @@
  *
  * What is written out here, and the passage each part follows:
  *   - ring candidates of a worker ......... Definition 1 (k-symmetric ring topology)
- *   - "randomly choose q neighbors" ....... Algorithm 1, sync branch, first statement;
+ *   - the random pick of q neighbours ..... Algorithm 1, sync branch, first statement;
  *                                           Section 2.2 last paragraph (fresh, independent
- *                                           choice per component and per sync)
+ *                                           choice per component and per sync); q may differ
+ *                                           from component to component (Algorithm 1's
+ *                                           REQUIRE lines only bound it by 2p)
  *   - neighbour average ................... Algorithm 1, the averaging statement
  *   - G, Delta, omega, theta updates ...... Algorithm 1, the four gossip-BMUF statements
  *   - gossip-MA branch .................... Algorithm 1, the gossip-MA statement
@@ -79,7 +81,7 @@ void gbmuf_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], ui
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-/* Section 3.3: p is chosen "empirically according to p = log2(n) - 1"; at least 1. */
+/* Section 3.3 gives the rule of thumb p = log2(n) - 1 for the ring degree; at least 1. */
 int32_t gbmuf_oracle_default_p(int32_t K)
 {
     int32_t lg = 0;
@@ -106,8 +108,8 @@ int32_t gbmuf_oracle_ring_candidates(int32_t w, int32_t K, int32_t p, int32_t *c
     return C;
 }
 
-/* Algorithm 1, "randomly choose q neighbors k_1..k_q", for worker w and component i in
- * sync number `round`.  out[0..q) ascending.  Returns ORACLE_EINVAL if q exceeds the
+/* Algorithm 1, sync branch, first statement: the random pick of q neighbours k_1..k_q for
+ * worker w and component i in sync number `round`.  out[0..q) ascending.  Returns ORACLE_EINVAL if q exceeds the
  * number of candidates (the paper requires q <= 2p). */
 int gbmuf_oracle_sample(int32_t K, int32_t p, int32_t q, uint64_t seed, uint64_t round,
                         int32_t w, int32_t i, int32_t *out)
@@ -155,18 +157,51 @@ int gbmuf_oracle_neighbour_table(int32_t m, int32_t K, int32_t p, int32_t q, uin
     return ORACLE_OK;
 }
 
-/* Common argument check of the sync functions below. */
-static int check_sync_args(const int64_t *off, int32_t m, int32_t K, int32_t q,
-                           const int32_t *nbr, const void *theta, int64_t stride)
+/* The same table when component i draws its own number q[i] of neighbours (Algorithm 1 only
+ * requires q <= 2p; Section 3.3 picks (p, q) per deployment).  Rows have `width` >= max q[i]
+ * entries: nbr[i][w][0..q[i]) are the chosen ids, ascending; the rest of the row is -1. */
+int gbmuf_oracle_neighbour_table_q(int32_t m, int32_t K, int32_t p, const int32_t *q,
+                                   int32_t width, uint64_t seed, uint64_t round, int32_t *nbr)
 {
-    if (!off || !theta || m < 0 || K < 1 || q < 0 || q > K - 1) return ORACLE_EINVAL;
-    if (q > 0 && m > 0 && !nbr) return ORACLE_EINVAL;
+    if (m < 0 || width < 0 || (m > 0 && !q)) return ORACLE_EINVAL;
+    for (int32_t i = 0; i < m; ++i)
+        if (q[i] < 0 || q[i] > width) return ORACLE_EINVAL;
+    for (int32_t i = 0; i < m; ++i)
+        for (int32_t w = 0; w < K; ++w) {
+            int32_t *row = nbr + ((size_t)i * (size_t)K + (size_t)w) * (size_t)width;
+            int rc = gbmuf_oracle_sample(K, p, q[i], seed, round, w, i, row);
+            if (rc != ORACLE_OK) return rc;
+            for (int32_t j = q[i]; j < width; ++j) row[j] = -1;
+        }
+    return ORACLE_OK;
+}
+
+/* Common argument check of the sync functions below. */
+static int check_sync_args(const int64_t *off, int32_t m, int32_t K, const int32_t *q,
+                           int32_t width, const int32_t *nbr, const void *theta, int64_t stride)
+{
+    if (!off || !theta || m < 0 || K < 1 || width < 0 || (m > 0 && !q)) return ORACLE_EINVAL;
     if (off[0] != 0) return ORACLE_EINVAL;
     for (int32_t i = 0; i < m; ++i) if (off[i + 1] < off[i]) return ORACLE_EINVAL;
     if (stride < off[m]) return ORACLE_EINVAL;
-    for (int64_t x = 0; nbr && x < (int64_t)m * K * q; ++x)
-        if (nbr[x] < 0 || nbr[x] >= K) return ORACLE_EINVAL;
+    for (int32_t i = 0; i < m; ++i) {
+        if (q[i] < 0 || q[i] > K - 1 || q[i] > width) return ORACLE_EINVAL;
+        if (q[i] > 0 && !nbr) return ORACLE_EINVAL;
+        for (int32_t w = 0; w < K; ++w)
+            for (int32_t j = 0; j < q[i]; ++j) {
+                int32_t v = nbr[((size_t)i * (size_t)K + (size_t)w) * (size_t)width + (size_t)j];
+                if (v < 0 || v >= K) return ORACLE_EINVAL;
+            }
+    }
     return ORACLE_OK;
+}
+
+/* q[0..m) = one value for every component. */
+static int32_t *uniform_q(int32_t m, int32_t q)
+{
+    int32_t *qv = (int32_t *)malloc(sizeof(int32_t) * (size_t)(m > 0 ? m : 1));
+    for (int32_t i = 0; qv && i < m; ++i) qv[i] = q;
+    return qv;
 }
 
 /* ids[0..q] = the worker itself and its q neighbours, ascending worker id. */
