@@ -3,11 +3,14 @@
 
 A step is one whole sync (neighbour sampling + fused gather-average-momentum kernel) over
 all components of all K workers of a synthetic LSTM-LM-shaped parameter set that is already
-resident in HBM.  Prints ONE JSON line: whole-job worker-params/s, the HBM roofline of the
-fused kernel (algorithmic bytes = 24 B per worker-param, launch durations measured live
-with events on the launch stream) and the CPU oracle timed on this machine's host cores.
+resident in HBM.  Prints ONE JSON line: whole-job worker-params/s of the headline workload
+(the largest benchmark configuration, K = 64), the HBM roofline of the fused kernel
+(algorithmic bytes = 24 B per worker-param, launch durations measured live with events on the
+launch stream around the very launches that are timed), the same figures for the other large
+configurations, and the CPU oracle timed on this machine's host cores.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|INDEX] [--all]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|INDEX] [--layout L]
+                    [--only] [--all] [--no-cpu] [--calibrate]
 """
 from __future__ import annotations
 
@@ -31,17 +34,30 @@ def log(*a):
 
 
 def measured_traffic(workload: str):
-    """HBM bytes per fused-kernel launch from the committed rocprofv3 --pmc summary, if any."""
-    path = os.path.join(ROOT, "profiles", f"sync_kernel_{workload}_pmc.md")
+    """HBM bytes per fused-kernel launch from the committed rocprofv3 --pmc summary of this
+    workload (a stored figure of an earlier profiled run, not of this run), and its file."""
+    rel = os.path.join("profiles", f"sync_kernel_{workload}_pmc.md")
     try:
-        m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(path).read(), re.M)
-        return float(m.group(1)) if m else None
+        m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", open(os.path.join(ROOT, rel)).read(), re.M)
+        return (float(m.group(1)), rel) if m else (None, None)
     except OSError:
-        return None
+        return None, None
 
 
-def run_gpu(w, steps: int, warmup: int, contiguous: bool = False):
-    import numpy as np
+def timed_launches(torch, stream, fn, n):
+    """n launches of fn(i), each between two events on the launch stream; mean ms."""
+    pairs = []
+    for i in range(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn(i)
+        e1.record(stream)
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in pairs) / max(n, 1)
+
+
+def run_gpu(w, steps: int, warmup: int, layout: str = "blocked", entry_points: bool = False):
     import torch
 
     from paper_1909_09010_amd import binding, workloads
@@ -51,110 +67,81 @@ def run_gpu(w, steps: int, warmup: int, contiguous: bool = False):
     P = int(off[-1])
     m = len(off) - 1
     t0 = time.perf_counter()
-    span = None if contiguous else workloads.default_span_bytes(dev, 3 * w.K * workloads.padded_stride(P) * 4)
-    theta, omega, delta = workloads.init_state(w, dev, span_bytes=span)
-    stride = theta.stride(0)
-    plan = binding.Plan(off, w.K, w.q, w.p, seed=w.seed)
-    torch.cuda.synchronize()
-    log(f"[bench] {w.name}: K={w.K} q={w.q} p={plan.info.p} P={P} m={m} tiles={plan.info.n_tiles} "
-        f"state={3 * w.K * theta.shape[1] * 4 / 1e9:.1f} GB, row stride {stride * 4 / 1e9:.2f} GB, "
-        f"HBM span {(w.K - 1) * stride * 4 / 1e9 + 3 * theta.shape[1] * 4 / 1e9:.0f} GB, init {time.perf_counter() - t0:.1f}s")
-    stream = torch.cuda.current_stream()
-
     H = workloads.periods(w)
-    if H is not None:
-        plan.set_periods(H)                     # Algorithm 1's per-component periods; a step is then one
-        tick = int(H.min())                     # sync of the components that are due (counter += min H_i)
-
-    rnd = 0
-    for _ in range(warmup):
-        if H is None:
-            plan.sync(theta, omega, delta, stride, w.eta, w.zeta, w.mode, rnd, stream)
-        else:
-            plan.sync_step(theta, omega, delta, stride, w.eta, w.zeta, w.mode, (rnd + 1) * tick, stream)
-        rnd += 1
+    plan = binding.Plan(off, w.K, w.q, w.p, seed=w.seed, periods=H)
+    st = workloads.init_state(w, dev, layout=layout, plan=plan)
     torch.cuda.synchronize()
+    log(f"[bench] {w.name}: K={w.K} q={w.q} p={plan.info.p} P={P} m={m} layout={layout} "
+        f"state={3 * w.K * P * 4 / 1e9:.1f} GB in {st.bytes / 1e9:.1f} GB of HBM, init {time.perf_counter() - t0:.1f}s")
+    stream = torch.cuda.current_stream()
+    tick = int(H.min()) if H is not None else 1   # with periods a step is one sync of the components that are due
+
+    def sync(rnd):
+        if st.layout == "separate":
+            t, o, d = st.arrays
+            if H is None:
+                plan.sync(t, o, d, st.worker_stride, w.eta, w.zeta, w.mode, rnd, stream)
+            else:
+                plan.sync_step(t, o, d, st.worker_stride, w.eta, w.zeta, w.mode, (rnd + 1) * tick, stream)
+        elif H is None:
+            plan.sync_state(st.desc(), w.eta, w.zeta, w.mode, rnd, stream)
+        else:
+            plan.sync_step_state(st.desc(), w.eta, w.zeta, w.mode, (rnd + 1) * tick, stream)
+
+    for r in range(warmup):
+        sync(r)
+    torch.cuda.synchronize()
+    # the timed region: `steps` whole syncs back to back; every sync also sits between two events
+    # on the launch stream, which gives the launch durations of the very same syncs
     t0 = time.perf_counter()
+    launch_ms = timed_launches(torch, stream, lambda i: sync(warmup + i), steps)
+    elapsed = time.perf_counter() - t0
     synced = 0
-    for _ in range(steps):
+    for i in range(steps):
         if H is None:
-            plan.sync(theta, omega, delta, stride, w.eta, w.zeta, w.mode, rnd, stream)
             synced += P
         else:
-            plan.sync_step(theta, omega, delta, stride, w.eta, w.zeta, w.mode, (rnd + 1) * tick, stream)
-            active = ((rnd + 1) * tick) % H == 0
-            synced += int((off[1:] - off[:-1])[active].sum())
-        rnd += 1
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+            synced += int((off[1:] - off[:-1])[((warmup + i + 1) * tick) % H == 0].sum())
+    finite = all(bool(torch.isfinite(st.get_row(0, k)).all()) for k in (0, w.K - 1))
+    res = dict(P=P, m=m, K=w.K, synced_per_step=synced / max(steps, 1), elapsed=elapsed, launch_ms=launch_ms,
+               finite=finite, layout=layout, hbm_bytes=st.bytes, steps=steps,
+               tile_columns=plan.info.tile_columns_blocked if layout == "blocked" else plan.info.tile_columns)
+    if entry_points:
+        # the two further kernels on the same state: the gossip-MA branch (theta only: 8 B per
+        # worker-param, sampler included) and the final model average (4(K+1) B per parameter)
+        out = torch.empty(P, device=dev)
+        ma_desc = st.desc(gossip_ma=True)
+        rows = st.layout == "separate"
 
-    # the dominant kernel alone: same kernel and launch shape through gbmuf_sync_table, with the
-    # round's table drawn beforehand; one event pair per launch on the launch stream
-    nbr = torch.zeros((m, w.K, max(w.q, 1)), dtype=torch.int32, device=dev)
-    pairs = []
-    for _ in range(steps):
-        plan.neighbours_device(rnd, nbr, stream)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        plan.sync_table(nbr, theta, omega, delta, stride, w.eta, w.zeta, w.mode, stream)
-        e1.record(stream)
-        pairs.append((e0, e1))
-        rnd += 1
-    torch.cuda.synchronize()
-    kernel_ms = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
-    finite = bool(torch.isfinite(theta[:, :P]).all())
+        def ma(i):
+            if rows:
+                plan.sync(st.arrays[0], None, None, st.worker_stride, 0.0, 1.0, binding.MODE_GOSSIP_MA, i, stream)
+            else:
+                plan.sync_state(ma_desc, 0.0, 1.0, binding.MODE_GOSSIP_MA, i, stream)
+
+        def fa(i):
+            if rows:
+                plan.final_average(st.arrays[0], st.worker_stride, out, stream)
+            else:
+                plan.final_average_state(ma_desc, out, stream)
+
+        ma(0), fa(0)
+        ma_ms = timed_launches(torch, stream, ma, 5)
+        fa_ms = timed_launches(torch, stream, fa, 5)
+        res["entry_points"] = {
+            "gossip_ma": {"ms": ma_ms, "algorithmic_bytes": 8 * w.K * P, "GBps": 8 * w.K * P / ma_ms / 1e6,
+                          "frac": 8 * w.K * P / ma_ms / 1e6 / HBM_PEAK_GBPS, "note": "whole sync: sampler + kernel"},
+            "final_average": {"ms": fa_ms, "algorithmic_bytes": 4 * (w.K + 1) * P, "GBps": 4 * (w.K + 1) * P / fa_ms / 1e6,
+                              "frac": 4 * (w.K + 1) * P / fa_ms / 1e6 / HBM_PEAK_GBPS}}
+        del out
     plan.destroy()
-    del theta, omega, delta, nbr
-    torch.cuda.empty_cache()
-    return dict(P=P, m=m, K=w.K, stride=stride, synced_per_step=synced / max(steps, 1), padded=workloads.padded_stride(P), elapsed=elapsed,
-                kernel_ms=kernel_ms, finite=finite, layout="contiguous" if span is None else "interleaved_rows")
-
-
-def run_other_entry_points(w, launches: int = 5):
-    """The two further kernels on the same workload: the gossip-MA branch (theta only: 8 B per
-    worker-param) and the final model average (4(K+1) B per parameter)."""
-    import numpy as np
-    import torch
-
-    from paper_1909_09010_amd import binding, workloads
-
-    dev = "cuda:0"
-    off = workloads.component_offsets(w)
-    P = int(off[-1])
-    span = workloads.default_span_bytes(dev, 3 * w.K * workloads.padded_stride(P) * 4)
-    theta, _, _, stride = workloads.alloc_state(w.K, P, dev, span_bytes=span)
-    theta.normal_(0, 0.02)
-    out = torch.empty(P, device=dev)
-    plan = binding.Plan(off, w.K, w.q, w.p, seed=w.seed)
-    stream = torch.cuda.current_stream()
-
-    def timed(fn):
-        fn(0)
-        pairs = []
-        for r in range(1, launches + 1):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            fn(r)
-            e1.record(stream)
-            pairs.append((e0, e1))
-        torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
-
-    ma = timed(lambda r: plan.sync(theta, None, None, stride, 0.0, 1.0, binding.MODE_GOSSIP_MA, r, stream))
-    fa = timed(lambda r: plan.final_average(theta, stride, out, stream))
-    plan.destroy()
-    res = {"gossip_ma": {"ms": ma, "algorithmic_bytes": 8 * w.K * P, "GBps": 8 * w.K * P / ma / 1e6,
-                         "frac": 8 * w.K * P / ma / 1e6 / HBM_PEAK_GBPS, "note": "whole sync: sampler + kernel"},
-           "final_average": {"ms": fa, "algorithmic_bytes": 4 * (w.K + 1) * P, "GBps": 4 * (w.K + 1) * P / fa / 1e6,
-                             "frac": 4 * (w.K + 1) * P / fa / 1e6 / HBM_PEAK_GBPS}}
-    del theta, out
+    del st
     torch.cuda.empty_cache()
     return res
 
 
 def run_copy_probe(n_floats: int = 1 << 28, launches: int = 3):
     """gbmuf_probe_copy on two 1 GiB buffers: 4*n bytes read and 4*n bytes written per launch."""
-    import numpy as np
     import torch
 
     from paper_1909_09010_amd import binding
@@ -163,15 +150,7 @@ def run_copy_probe(n_floats: int = 1 << 28, launches: int = 3):
     dst = torch.empty_like(src)
     stream = torch.cuda.current_stream()
     binding.probe_copy(dst, src, n_floats, 0, stream)
-    pairs = []
-    for _ in range(launches):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        binding.probe_copy(dst, src, n_floats, 0, stream)
-        e1.record(stream)
-        pairs.append((e0, e1))
-    torch.cuda.synchronize()
-    ms = float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+    ms = timed_launches(torch, stream, lambda i: binding.probe_copy(dst, src, n_floats, 0, stream), launches)
     assert torch.equal(src, dst)
     return {"bytes_read": 4 * n_floats, "bytes_written": 4 * n_floats, "ms": ms, "GBps": 8 * n_floats / ms / 1e6}
 
@@ -186,7 +165,7 @@ def run_cpu_baseline(w, target_seconds: float = 15.0):
 
     off = workloads.component_offsets(w)
     P = int(off[-1])
-    budget = 4_000_000                                  # sampled parameters per worker
+    budget = 16_000_000 // w.K * 4                      # sampled parameters per worker (64 M worker-params)
     frac = min(1.0, budget / P)
     sizes = np.maximum(1, np.floor((off[1:] - off[:-1]) * frac)).astype(np.int64)
     sizes = np.minimum(sizes, off[1:] - off[:-1])
@@ -212,20 +191,33 @@ def run_cpu_baseline(w, target_seconds: float = 15.0):
                       f"({Ps} params/worker, K={w.K}), {rounds} rounds in {dt:.1f}s, fp32 C oracle with OpenMP"}
 
 
+def summary(w, g):
+    """One workload's figures: whole-sync throughput and the launch-duration roofline."""
+    wp_synced = g["K"] * g["synced_per_step"]
+    v = wp_synced * g["steps"] / g["elapsed"]
+    # the launch covers the tiles of the components that were due: its algorithmic bytes
+    gbps = BYTES_PER_WORKER_PARAM * wp_synced / (g["launch_ms"] * 1e-3) / 1e9
+    return {"workload": w.name, "K": w.K, "q": w.q, "params_per_worker": g["P"], "components": g["m"],
+            "layout": g["layout"], "state_GB": 3 * w.K * g["P"] * 4 / 1e9, "arena_GB": g["hbm_bytes"] / 1e9,
+            "value": v, "ms_per_step": g["elapsed"] / g["steps"] * 1e3, "kernel_ms": g["launch_ms"],
+            "kernel_GBps": gbps, "kernel_frac": gbps / HBM_PEAK_GBPS, "steps": g["steps"]}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="large_vocab",
-                    help="name or index into the benchmark configurations (default: configs[2], large_vocab)")
-    ap.add_argument("--all", action="store_true", help="also time configs[1], [3], [4] and the 4-layer K=64 variant")
+    ap.add_argument("--workload", default="k64",
+                    help="name or index into the benchmark configurations (default: configs[4], k64, the largest)")
+    ap.add_argument("--layout", default="blocked", choices=["blocked", "rows", "separate"],
+                    help="state placement: the library's blocked arena (default), its rows arena, or three separate tensors")
+    ap.add_argument("--only", action="store_true", help="time the headline workload only (what the profiles run)")
+    ap.add_argument("--all", action="store_true", help="also time configs[0], [1] and the paper-shaped (16,128) schedule")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the library's plain copy probe (1 GiB read + 1 GiB written per launch): "
                          "the known-traffic kernel that rocprofv3 byte counters are scaled by")
-    ap.add_argument("--contiguous", action="store_true",
-                    help="three separate contiguous [K, P] tensors instead of the HBM-spanning row layout")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (K workers are replicas in one GPU's HBM); "
@@ -241,24 +233,19 @@ def main() -> int:
         return 3
 
     w = workloads.get(args.workload)
-    gc = None
-    if args.all and not args.contiguous:
-        # the same workload with the rows side by side, measured first: physical placement depends on
-        # what the process allocated before, and a fresh process is what a caller of this layout gets
-        gc = run_gpu(w, min(args.steps, 5), args.warmup, contiguous=True)
-    g = run_gpu(w, args.steps, args.warmup, args.contiguous)
-    wp = g["K"] * g["P"]
-    value = wp * args.steps / g["elapsed"]
-    algo_bytes = BYTES_PER_WORKER_PARAM * wp
-    achieved = algo_bytes / (g["kernel_ms"] * 1e-3) / 1e9
+    g = run_gpu(w, args.steps, args.warmup, args.layout, entry_points=not args.only)
+    head = summary(w, g)
+    assert head["kernel_ms"] <= head["ms_per_step"] * 1.001, "event-timed launches cannot exceed the wall clock around them"
+    algo_bytes = BYTES_PER_WORKER_PARAM * w.K * g["P"]
+    traffic, traffic_src = measured_traffic(w.name) if args.layout == "blocked" else (None, None)
     out = {
         "metric": "gossip_bmuf_sync_worker_params_per_s",
-        "value": value,
+        "value": head["value"],
         "unit": "worker-params/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": g["elapsed"] / args.steps * 1e3,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -266,33 +253,35 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "K": w.K, "q": w.q, "params_per_worker": g["P"], "components": g["m"],
                    "eta": w.eta, "zeta": w.zeta, "mode": "nesterov" if w.mode == 1 else str(w.mode),
-                   "state_GB": 3 * w.K * g["padded"] * 4 / 1e9, "layout": g["layout"],
-                   "row_stride_GB": g["stride"] * 4 / 1e9},
-        "effective_GBps": BYTES_PER_WORKER_PARAM * value / 1e9,
-        "pct_of_hbm_peak": 100.0 * BYTES_PER_WORKER_PARAM * value / 1e9 / HBM_PEAK_GBPS,
+                   "state_GB": head["state_GB"], "arena_GB": head["arena_GB"], "layout": g["layout"],
+                   "tile_columns": g["tile_columns"]},
+        "effective_GBps": BYTES_PER_WORKER_PARAM * head["value"] / 1e9,
+        "pct_of_hbm_peak": 100.0 * BYTES_PER_WORKER_PARAM * head["value"] / 1e9 / HBM_PEAK_GBPS,
         "finite": g["finite"],
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(w.name),
-                     "kernel": "sync_vec4_kernel", "kernel_ms": g["kernel_ms"], "algorithmic_bytes": algo_bytes},
+        "roofline": {"bound": "hbm", "achieved": head["kernel_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": head["kernel_frac"], "traffic": traffic, "traffic_source": traffic_src,
+                     "kernel": "sync_vec4_kernel", "kernel_ms": head["kernel_ms"], "algorithmic_bytes": algo_bytes,
+                     "timing": "mean over the timed syncs, each between two events on the launch stream "
+                               "(the few-microsecond sampler launch of a sync is inside)"},
     }
-    if args.all:
+    if "entry_points" in g:
+        out["other_entry_points"] = g["entry_points"]
+    if not args.only:
+        names = ["large_vocab", "large_vocab_chunked", "k64", "k64_4layer"]
+        if args.all:
+            names += ["tiny", "medium", "paper_shaped"]
         others = []
-        for name in ("tiny", "medium", "large_vocab_chunked", "k64", "k64_4layer", "paper_shaped"):
+        for name in names:
             if name == w.name:
                 continue
             ww = workloads.get(name)
-            steps = min(args.steps, ww.rounds)
-            gg = run_gpu(ww, steps, args.warmup, args.contiguous)
-            v = gg["K"] * gg["synced_per_step"] * steps / gg["elapsed"]   # worker-params actually synced
-            kb = BYTES_PER_WORKER_PARAM * gg["K"] * gg["P"] / (gg["kernel_ms"] * 1e-3) / 1e9
-            others.append({"workload": name, "value": v, "ms_per_step": gg["elapsed"] / steps * 1e3,
-                           "effective_GBps": BYTES_PER_WORKER_PARAM * v / 1e9, "kernel_GBps": kb,
-                           "kernel_frac": kb / HBM_PEAK_GBPS})
+            others.append(summary(ww, run_gpu(ww, min(args.steps, ww.rounds, 10), args.warmup, args.layout)))
         out["other_workloads"] = others
-        out["other_entry_points"] = run_other_entry_points(w)
-        if gc is not None:
-            out["contiguous_layout"] = {"kernel_ms": gc["kernel_ms"],
-                                        "kernel_frac": BYTES_PER_WORKER_PARAM * wp / (gc["kernel_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        if args.layout == "blocked":
+            # what a caller with three plain [K, P] tensors gets (rows: 3K address streams; the
+            # figure then depends on where the driver happened to place the tensors)
+            sep = summary(w, run_gpu(w, min(args.steps, 5), args.warmup, "separate"))
+            out["separate_tensors_layout"] = {k: sep[k] for k in ("kernel_ms", "kernel_GBps", "kernel_frac", "arena_GB")}
     if args.calibrate:
         out["copy_probe"] = run_copy_probe()
     if not args.no_cpu:

@@ -7,8 +7,8 @@
  * (arXiv 1909.09010), applied to all K nodes at once:
  *
  *   for every component i and worker w:
- *       choose q of w's ring neighbours at random            (Alg. 1, sync branch; Def. 1)
- *       avg   = (theta[w] + sum_j theta[k_j]) / (q+1)         (Alg. 1, averaging statement)
+ *       choose q_i of w's ring neighbours at random          (Alg. 1, sync branch; Def. 1)
+ *       avg   = (theta[w] + sum_j theta[k_j]) / (q_i+1)       (Alg. 1, averaging statement)
  *       G     = avg - theta_{t-H}[w]                          (Alg. 1, gossip-BMUF statements)
  *       Delta = eta*Delta + zeta*G
  *       omega = omega + Delta
@@ -20,16 +20,25 @@
  *   - "host" pointers are ordinary process memory; "device" pointers are HIP device
  *     memory of the GPU that was current when the plan was made.  The caller owns every
  *     buffer it passes; the library copies what it keeps.
- *   - Parameter buffers are K rows of `worker_stride` floats (row w = worker w); the first
- *     P = comp_offsets[m] floats of a row are parameters, the rest is never touched.
- *     Component i is elements [comp_offsets[i], comp_offsets[i+1]).  No alignment is
- *     required; 16-byte aligned bases with worker_stride % 4 == 0 take the 16-byte path, and
- *     bases and strides that are multiples of 1 KB (4 KB to be safe) let every tile of the
- *     kernel cover whole cache lines, which is worth about a quarter of the bandwidth.
+ *   - A plan is immutable once made: every call takes it as const, and calls on one plan
+ *     may run concurrently from several host threads.
+ *   - Where the state lives (two layouts, see gbmuf_state_t):
+ *       rows     K rows of `worker_stride` floats per array (row w = worker w); the first
+ *                P = comp_offsets[m] floats of a row are parameters, the rest is never
+ *                touched.  This is what the calls without "_state" in their name take.
+ *       blocked  every row is cut into blocks of B floats and the blocks with the same index
+ *                of all workers (and, if the caller wishes, of all three arrays) sit next to
+ *                each other, so that what one workgroup streams is one short address range.
+ *                This is the fast layout on MI355X (see gbmuf_recommend_layout).
+ *     Component i is elements [comp_offsets[i], comp_offsets[i+1]) of every worker.  No
+ *     alignment is required; 16-byte aligned bases with strides that are multiples of 4
+ *     floats take the 16-byte path, and rows (blocks) that start on multiples of 4 KB let
+ *     every tile of the kernel cover whole cache lines.
  *   - All parameter arithmetic is IEEE binary32, round to nearest even, every multiply and
  *     add rounded separately (no fused multiply-add).  Sampling is integer only.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device work is
- *     only ordered by that stream; no call synchronises the host except where stated.
+ *     only ordered by that stream; no call synchronises the host except gbmuf_plan_create /
+ *     gbmuf_plan (blocking uploads of the small tables) and gbmuf_plan_destroy.
  *   - On a machine without a GPU a plan can still be made and the host-side calls work;
  *     the device calls then return GBMUF_EDEVICE.
  */
@@ -63,37 +72,87 @@ enum {
 
 #define GBMUF_MAX_K 1024       /* workers per plan */
 
+/* Where the neighbour rows of a sync are drawn (gbmuf_plan_desc_t.sampling). */
+enum {
+    GBMUF_SAMPLING_AUTO = 0,      /* in the fused kernel for small, launch-bound plans, else separate */
+    GBMUF_SAMPLING_IN_KERNEL = 1, /* every workgroup draws its component's rows itself (one launch)  */
+    GBMUF_SAMPLING_SEPARATE = 2   /* a sampler kernel fills a table first (two launches)            */
+};
+
+/* In which direction the fused kernel walks its tile list (gbmuf_plan_desc_t.sweep). */
+enum {
+    GBMUF_SWEEP_AUTO = 0,         /* even rounds forwards, odd rounds backwards: what a sync wrote
+                                     last is read first by the next one, while still in cache      */
+    GBMUF_SWEEP_FORWARD = 1       /* always forwards */
+};
+
+/*
+ * Everything a plan is made from.  Zero the struct, set struct_size = sizeof(gbmuf_plan_desc_t)
+ * and fill in what is needed; every field whose value is 0 / NULL takes the library's default.
+ * (Section 2.2: theta = [theta_1 .. theta_m]; Definition 1: p-symmetric ring; Alg. 1 REQUIRE
+ * lines: components, sync periods H_i, q <= 2p; Section 3.3: (p, q) per deployment.)
+ */
+typedef struct gbmuf_plan_desc {
+    uint32_t struct_size;           /* sizeof(gbmuf_plan_desc_t) of the caller's header           */
+    int32_t m;                      /* components, >= 0                                           */
+    int32_t K;                      /* workers, 1 .. GBMUF_MAX_K                                  */
+    int32_t q;                      /* neighbours drawn per component and sync, 0 <= q <= C;
+                                       used for every component unless q_per_component is set     */
+    const int64_t *comp_offsets;    /* host, m+1 element offsets: [0] = 0, non-decreasing (an
+                                       empty component is allowed).  Copied.                      */
+    const int32_t *q_per_component; /* host, m entries 0 <= q_i <= C, or NULL.  Copied.           */
+    const int32_t *periods;         /* host, m sync periods H_i >= 1 for gbmuf_sync_step, or NULL
+                                       (every component syncs at every step).  Copied.            */
+    int32_t p;                      /* ring degree.  0 = the paper's rule p = log2(K) - 1 (floor,
+                                       at least 1; Section 3.3); -1 = every other worker is a
+                                       candidate.  Values above K-1 mean K-1 (the listing of
+                                       Definition 1 is complete by then).                         */
+    int32_t reserved0;
+    uint64_t seed;                  /* sampler key; with `round` it fixes every neighbour table   */
+    /* ---- tuning; none of these changes a result bit ---- */
+    int32_t tile_threads;           /* threads per workgroup of the fused kernel: 256, 512, 1024  */
+    int32_t tile_slots;             /* 16-byte slots per thread: 1, 2, 4, 8, 16.  Both 0 = chosen
+                                       by K and layout; a pair that is not built in -> EINVAL     */
+    int32_t sampling;               /* GBMUF_SAMPLING_*                                           */
+    int32_t sweep;                  /* GBMUF_SWEEP_*                                              */
+    int32_t cache_hints;            /* bit 0: non-temporal stores, bit 1: non-temporal loads      */
+    int32_t workgroups_per_cu;      /* upper bound on the fused kernel's resident workgroups per
+                                       compute unit (enforced through its LDS request); 0 = by
+                                       layout: none for rows, a small number for blocked state    */
+} gbmuf_plan_desc_t;
+
 /* What a plan was made with (after defaults were resolved) and how it will run. */
 typedef struct gbmuf_info {
-    int32_t m, K, q;
-    int32_t p;              /* ring degree actually used                                  */
-    int32_t C;              /* ring candidates per worker = min(2p, K-1)                  */
-    int32_t has_device;     /* 1 if device calls are available                            */
-    int64_t P;              /* parameters per worker = comp_offsets[m]                    */
-    int64_t n_tiles;        /* workgroups one sync launches                               */
-    int32_t tile_columns;   /* 16-byte columns (4 floats) of one worker row per workgroup */
-    int32_t threads;        /* threads per workgroup of the fused kernel                  */
+    int32_t m, K;
+    int32_t q;              /* neighbours per component; the largest q_i if they differ      */
+    int32_t p;              /* ring degree actually used                                     */
+    int32_t C;              /* ring candidates per worker = min(2p, K-1)                     */
+    int32_t has_device;     /* 1 if device calls are available                               */
+    int64_t P;              /* parameters per worker = comp_offsets[m]                       */
+    int64_t n_tiles;        /* workgroups one sync of all components launches                */
+    int32_t tile_columns;   /* 16-byte columns (4 floats) of one worker row per workgroup    */
+    int32_t threads;        /* threads per workgroup of the fused kernel                     */
     uint64_t seed;
+    int32_t mixed_q;        /* 1 if components draw different numbers of neighbours          */
+    int32_t has_periods;    /* 1 if sync periods were given                                  */
+    int32_t in_kernel_sampling; /* 1 if gbmuf_sync draws the rows inside the fused kernel    */
+    int32_t tile_columns_blocked, threads_blocked;   /* the same for blocked state           */
+    int32_t workgroups_per_cu_blocked;               /* resident workgroups per CU, blocked  */
 } gbmuf_info_t;
 
 /*
- * gbmuf_plan -- partition, topology and sampler key for a series of syncs.
- * (Section 2.2: theta = [theta_1 .. theta_m]; Definition 1: p-symmetric ring; Alg. 1
- * REQUIRE lines: components, q <= 2p.)
- *   out           receives the plan; destroy it with gbmuf_plan_destroy.
- *   comp_offsets  host, m+1 entries, element offsets: [0] = 0, non-decreasing (an empty
- *                 component is allowed).  Copied.
- *   m, K          components (>= 0) and workers (1 .. GBMUF_MAX_K).
- *   q             neighbours drawn per component and sync, 0 <= q <= C.
- *   p             ring degree.  0 = the paper's rule p = log2(K) - 1 (floor, at least 1;
- *                 Section 3.3); -1 = floor(K/2): every other worker is a candidate.
- *   seed          sampler key; with `round` it fixes every neighbour table.
- * Errors: EINVAL (NULLs, K < 1, m < 0, bad offsets, q < 0 or q > C, p < -1),
- * EUNSUPPORTED (K > GBMUF_MAX_K, or K*(q+1) too large for the on-chip neighbour rows),
- * ENOMEM, EDEVICE (a GPU is present but a HIP call failed).
- * If a GPU is present the plan allocates its small device tables (candidates, tile list,
- * neighbour scratch) on the current device; sync calls allocate nothing.
+ * gbmuf_plan_create -- partition, topology, sampler key, neighbour counts and sync periods
+ * for a series of syncs.
+ * Errors: EINVAL (NULLs, struct_size too small, K < 1, m < 0, bad offsets, q or q_i < 0 or
+ * > C, p < -1, H_i < 1, unknown enum or tile shape), EUNSUPPORTED (K > GBMUF_MAX_K, or the
+ * neighbour rows of all workers do not fit on chip beside a tile), ENOMEM, EDEVICE (a GPU is
+ * present but a HIP call failed).
+ * If a GPU is present the plan allocates its small device tables (candidates, tile lists,
+ * per-component table, neighbour scratch) on the current device; sync calls allocate nothing.
  */
+int gbmuf_plan_create(gbmuf_plan_t **out, const gbmuf_plan_desc_t *desc);
+
+/* The short form: one q for all components, no periods, default tuning. */
 int gbmuf_plan(gbmuf_plan_t **out, const int64_t *comp_offsets, int32_t m, int32_t K,
                int32_t q, int32_t p, uint64_t seed);
 
@@ -111,19 +170,41 @@ int gbmuf_plan_info(const gbmuf_plan_t *plan, gbmuf_info_t *info);
 int gbmuf_candidates_host(const gbmuf_plan_t *plan, int32_t w, int32_t *out_host);
 
 /*
- * Neighbour table of sync number `round`: int32 [m][K][q], each row ascending, drawn
- * uniformly without replacement from the worker's candidates, independently for every
- * (component, worker, round) (Alg. 1 "randomly choose q neighbors"; Section 2.2, last
- * paragraph).  The host and the device version return the same bits.
- * gbmuf_neighbours_device enqueues on `stream` and writes device memory out_dev.
+ * Neighbour table of sync number `round`: int32 [m][K][q] with q = gbmuf_info_t.q (the
+ * largest q_i).  Row (i, w) holds the q_i ids worker w drew for component i, ascending, drawn
+ * uniformly without replacement from the worker's candidates and independently for every
+ * (component, worker, round) (Alg. 1, sync branch, first statement; Section 2.2, last
+ * paragraph); entries beyond q_i are -1.  The host and the device version return the same
+ * bits.  gbmuf_neighbours_device enqueues on `stream` and writes device memory out_dev.
  */
 int gbmuf_neighbours_host(const gbmuf_plan_t *plan, uint64_t round, int32_t *out_host);
 int gbmuf_neighbours_device(const gbmuf_plan_t *plan, uint64_t round, int32_t *out_dev,
                             void *stream);
 
 /*
- * gbmuf_sync -- one synchronisation of all components of all K workers, in place.
- * (Alg. 1, the whole sync branch.)
+ * Where the three state arrays are.  Element e (0 <= e < P) of worker w of array X is the
+ * float at
+ *     X + w * worker_stride + e                                         if block_floats == 0
+ *     X + (e / B) * block_stride + w * worker_stride + (e % B)          if block_floats == B > 0
+ * rows:     worker_stride >= P.
+ * blocked:  B a power of two, at least 4 * tile_columns_blocked and at most 2^30;
+ *           worker_stride >= B; block_stride >= (K-1) * worker_stride + B.  The last block
+ *           of a row may be partly unused; those floats are never touched.
+ * theta, omega, delta: device, in/out.  omega and delta may be NULL only with
+ * GBMUF_MODE_GOSSIP_MA.  The floats the three arrays cover must not overlap (checked: EINVAL).
+ */
+typedef struct gbmuf_state {
+    float *theta;            /* the replicas                                   */
+    float *omega;            /* per-worker "global model" slot                 */
+    float *delta;            /* block-momentum slot                            */
+    int64_t worker_stride;
+    int64_t block_floats;
+    int64_t block_stride;
+} gbmuf_state_t;
+
+/*
+ * gbmuf_sync -- one synchronisation of all components of all K workers, in place, state in
+ * rows.  (Alg. 1, the whole sync branch.)
  *   replicas  device, in/out: theta, K rows.
  *   global    device, in/out: omega (the per-worker "global model" slot), K rows.
  *   delta     device, in/out: Delta (block momentum slot), K rows.
@@ -135,76 +216,100 @@ int gbmuf_neighbours_device(const gbmuf_plan_t *plan, uint64_t round, int32_t *o
  *   round          0-based sync counter; selects the neighbour table.
  * Every average uses the workers' values from before the call (snapshot semantics), the
  * sum runs over the worker and its neighbours in ascending worker id and is multiplied by
- * the rounded constant 1/(q+1).  The three buffers must not overlap.  The call enqueues
- * one or two kernels on `stream` and returns; it allocates nothing.  Two syncs on the same
- * plan must not run concurrently on different streams (large plans draw the neighbour table
- * into the plan's scratch with a separate kernel; small, launch-bound plans draw it inside
- * the fused kernel and use no scratch).  Errors: EINVAL (NULLs, worker_stride < P, unknown mode), EDEVICE.
+ * the rounded constant 1/(q_i+1).  The call enqueues one or two kernels on `stream` and
+ * returns; it allocates nothing.  Two syncs on the same plan must not be in flight at the
+ * same time on different streams unless the plan samples in the kernel (the sampler kernel
+ * writes the plan's one neighbour scratch).
+ * Errors: EINVAL (NULLs, worker_stride < P, unknown mode, overlapping arrays), EDEVICE.
+ * gbmuf_sync_state is the same for any gbmuf_state_t.
  */
 int gbmuf_sync(const gbmuf_plan_t *plan, float *replicas, float *global, float *delta,
                int64_t worker_stride, float eta, float zeta, int32_t nesterov,
                uint64_t round, void *stream);
+int gbmuf_sync_state(const gbmuf_plan_t *plan, const gbmuf_state_t *state, float eta,
+                     float zeta, int32_t nesterov, uint64_t round, void *stream);
 
 /*
  * Same update with the neighbours given by the caller: nbr_dev is device memory,
- * int32 [m][K][q], ids in [0, K) (rows need not be sorted; an id outside [0, K) is clamped
- * into range, the result is then unspecified but memory-safe).  A row should hold distinct
- * ids different from the worker.  Used to check the arithmetic against enumerated tables.
+ * int32 [m][K][q] (q = gbmuf_info_t.q; component i uses the first q_i entries of a row).
+ * Rows need not be sorted; an id outside [0, K) is clamped into range, the result is then
+ * unspecified but memory-safe.  A row should hold distinct ids different from the worker.
+ * Used to check the arithmetic against enumerated tables.
  */
 int gbmuf_sync_table(const gbmuf_plan_t *plan, const int32_t *nbr_dev, float *replicas,
                      float *global, float *delta, int64_t worker_stride, float eta,
                      float zeta, int32_t nesterov, void *stream);
+int gbmuf_sync_table_state(const gbmuf_plan_t *plan, const int32_t *nbr_dev,
+                           const gbmuf_state_t *state, float eta, float zeta,
+                           int32_t nesterov, void *stream);
 
 /*
- * Per-component synchronisation periods (Algorithm 1: component i takes the sync branch only
- * when t mod H_i == 0; Section 3.3 uses (16,128): embedding shards every 128 mini-batches,
- * the rest every 16).
- * gbmuf_plan_set_periods stores H_i >= 1 for the m components (host array, copied; NULL
- * clears them, i.e. every component syncs).  It synchronises the device and must not run
- * concurrently with syncs on the same plan.  EINVAL for NULL plan or H_i < 1.
- * gbmuf_sync_step is gbmuf_sync for mini-batch counter `step`: only the components with
- * step mod H_i == 0 are updated, the others are not read or written; the neighbour tables
- * are those of round = step, so every sync of every component draws fresh neighbours
- * (Section 2.2, last paragraph).  Without periods it equals gbmuf_sync(round = step).
- * Contiguous runs of active components are launched as ranges of the tile list (up to 8
- * runs); a more scattered schedule takes one launch that checks the period on the device.
+ * gbmuf_sync_step -- gbmuf_sync for mini-batch counter `step` under the plan's sync periods
+ * (Algorithm 1: component i takes the sync branch only when t mod H_i == 0; Section 3.3 uses
+ * (16,128): embedding shards every 128 mini-batches, the rest every 16).  Only the
+ * components with step mod H_i == 0 are sampled and updated, the others are neither read nor
+ * written; the neighbour tables are those of round = step, so every sync of every component
+ * draws fresh neighbours (Section 2.2, last paragraph).  A plan without periods syncs every
+ * component: the call then equals gbmuf_sync(round = step).
+ * When the components that are due form one run of consecutive components (the (16,128)
+ * schedule does), the kernels are launched over exactly that run; otherwise one launch covers
+ * all tiles and the workgroups of components that are not due return at once.
  */
-int gbmuf_plan_set_periods(gbmuf_plan_t *plan, const int32_t *periods_host);
 int gbmuf_sync_step(const gbmuf_plan_t *plan, float *replicas, float *global, float *delta,
                     int64_t worker_stride, float eta, float zeta, int32_t nesterov,
                     uint64_t step, void *stream);
+int gbmuf_sync_step_state(const gbmuf_plan_t *plan, const gbmuf_state_t *state, float eta,
+                          float zeta, int32_t nesterov, uint64_t step, void *stream);
 
 /*
  * Final model of Algorithm 1 (RETURN statement): out_dev[e] = (1/K) * sum_k replicas[k][e]
  * for e < P, summed in ascending worker id and multiplied by the rounded constant 1/K.
- * replicas: device, K rows of worker_stride floats (read only); out_dev: device, P floats.
- * 16-byte aligned pointers with worker_stride % 4 == 0 take 16-byte loads.
+ * replicas: device, read only; out_dev: device, P contiguous floats, not overlapping the
+ * replicas.  gbmuf_final_average_state reads state->theta in the state's layout (omega and
+ * delta are ignored).
  */
 int gbmuf_final_average(const gbmuf_plan_t *plan, const float *replicas, int64_t worker_stride,
                         float *out_dev, void *stream);
+int gbmuf_final_average_state(const gbmuf_plan_t *plan, const gbmuf_state_t *state,
+                              float *out_dev, void *stream);
 
 /*
- * Placement advice for the three state buffers (host only, no GPU needed).  The ABI takes
- * three base pointers and one row stride, so rows may be placed anywhere; on MI355X the
- * sync kernel is measurably faster (about 62 % -> 75 % of peak HBM bandwidth) when the 3K
- * rows it streams concurrently are spread over much more than ~70 GB of HBM instead of
- * sitting side by side.  The layout returned is ONE arena of arena_floats floats holding
- * [theta_w | omega_w | delta_w | gap] for w = 0..K-1:
- *     theta = arena, omega = arena + omega_offset, delta = arena + delta_offset,
- *     row w of each at + w * worker_stride.
- * span_bytes is the HBM the K rows should cover (e.g. 150e9 on a 288 GB device); the stride
- * is never smaller than three padded rows, so span_bytes = 0 gives the dense interleaving.
- * Rows are padded to a multiple of 1024 floats (4 KB) and so is the stride: with rows on
- * 4 KB boundaries the kernel's tiles cover whole cache lines.
- * EINVAL for P < 0, K < 1, span_bytes < 0 or NULL out.
+ * Placement advice for the three state arrays (host only, no GPU needed).  Both layouts
+ * returned are ONE arena of arena_floats floats, exactly the state's size apart from padding
+ * of the last block or row:
+ *     state.theta = arena, state.omega = arena + omega_offset, state.delta = arena + delta_offset
+ * GBMUF_LAYOUT_BLOCKED (recommended): blocks of block_floats floats; the blocks with one index
+ *   lie together as [theta: K blocks | omega: K blocks | delta: K blocks], then the next index.
+ *   The fused kernel then streams ONE moving address range instead of 3K, keeps few workgroups
+ *   resident per compute unit so that this range stays short, and runs at the same speed
+ *   wherever the driver placed the arena.
+ * GBMUF_LAYOUT_ROWS: K groups [theta_w | omega_w | delta_w] of rows padded to 4 KB.  With rows
+ *   the kernel streams 3K ranges; measured bandwidth then depends on the physical placement the
+ *   allocation happens to get (about 61 % or 73 % of peak for a 53 GB state).
+ * EINVAL for P < 0, K < 1, an unknown kind or NULL out; EINVAL too if plan is not NULL and its
+ * K or P differ.  With a plan the block size suits that plan's tile shape; with NULL it suits
+ * every built-in shape.
  */
+enum { GBMUF_LAYOUT_ROWS = 0, GBMUF_LAYOUT_BLOCKED = 1 };
 typedef struct gbmuf_layout {
-    int64_t worker_stride;   /* floats between consecutive workers' rows          */
-    int64_t omega_offset;    /* floats from the arena start to omega's first row  */
-    int64_t delta_offset;    /* floats from the arena start to delta's first row  */
+    int64_t worker_stride;   /* gbmuf_state_t.worker_stride                       */
+    int64_t block_floats;    /* gbmuf_state_t.block_floats (0 for rows)           */
+    int64_t block_stride;    /* gbmuf_state_t.block_stride (0 for rows)           */
+    int64_t omega_offset;    /* floats from the arena start to omega              */
+    int64_t delta_offset;    /* floats from the arena start to delta              */
     int64_t arena_floats;    /* floats to allocate                                */
 } gbmuf_layout_t;
-int gbmuf_recommend_layout(int64_t P, int32_t K, int64_t span_bytes, gbmuf_layout_t *out);
+int gbmuf_recommend_layout(const gbmuf_plan_t *plan, int64_t P, int32_t K, int32_t kind,
+                           gbmuf_layout_t *out);
+
+/*
+ * Copies the parameters (elements e < P of every worker) of the arrays selected by `which`
+ * (bit 0 theta, bit 1 omega, bit 2 delta) from one placement to another, e.g. rows -> blocked
+ * before a series of syncs and back afterwards.  Both states are device memory; a selected
+ * array must be non-NULL in both and the two states must not overlap.  Enqueues on `stream`.
+ */
+int gbmuf_state_copy(const gbmuf_plan_t *plan, const gbmuf_state_t *dst, const gbmuf_state_t *src,
+                     int32_t which, void *stream);
 
 /*
  * Calibration probe, not part of the method: a plain streaming copy of n_floats floats

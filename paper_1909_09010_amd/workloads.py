@@ -140,71 +140,151 @@ def padded_stride(P: int, multiple: int = 1024) -> int:
     return (P + multiple - 1) // multiple * multiple
 
 
-def alloc_state(K: int, P: int, device, span_bytes: Optional[int] = None, stride: Optional[int] = None):
-    """Uninitialised theta, omega, delta as [K, P_padded] float32 views plus their row stride.
+class DeviceState:
+    """theta, omega, delta of K workers on a device, in one of three placements, plus the
+    plumbing tests and benchmarks need to move values in and out (no arithmetic of the method).
 
-    span_bytes None: three separate contiguous tensors (row stride = ``stride`` or P rounded
-    up to 1024 floats = 4 KB, so that every row starts on a 4 KB boundary).  span_bytes set: ONE arena in which worker w's three rows sit side by side,
-    [theta_w | omega_w | delta_w | gap], with the row stride chosen so that the K rows cover
-    about span_bytes of HBM.  On MI355X the sync kernel is measurably faster when the rows it
-    streams concurrently are spread over much more than ~70 GB of HBM address space (more
-    independent DRAM banks); 150 GB is a good span for every benchmark configuration.
+    layout "blocked": ONE arena [block][theta|omega|delta][worker][B floats]  (the library's
+                      recommended placement, gbmuf_recommend_layout)
+    layout "rows":    ONE arena [worker][theta|omega|delta][row padded to 4 KB]
+    layout "separate": three separate [K, stride] tensors (stride = P padded to 4 KB unless given)
     """
-    dev = torch.device(device)
-    Pp = padded_stride(P) if stride is None else stride
-    assert Pp >= P
-    if span_bytes is None:
-        return [torch.empty((K, Pp), device=dev, dtype=torch.float32) for _ in range(3)] + [Pp]
-    assert stride is None
-    from . import binding                       # the layout rule lives in the library
-    lay = binding.recommend_layout(P, K, int(span_bytes))
-    arena = torch.empty(lay.arena_floats, device=dev, dtype=torch.float32)
-    S = lay.worker_stride
-    views = [torch.as_strided(arena, (K, Pp), (S, 1), o) for o in (0, lay.omega_offset, lay.delta_offset)]
-    return views + [S]
+
+    def __init__(self, K: int, P: int, device, layout: str = "blocked", stride: Optional[int] = None, plan=None):
+        from . import binding
+        self.K, self.P, self.layout = K, P, layout
+        dev = torch.device(device)
+        self.block_floats = self.block_stride = 0
+        if layout == "separate":
+            Pp = padded_stride(P) if stride is None else stride
+            assert Pp >= P
+            self.arena = None
+            self.arrays = [torch.empty((K, Pp), device=dev, dtype=torch.float32) for _ in range(3)]
+            self.worker_stride = Pp
+            self.width = Pp
+        else:
+            assert stride is None
+            kind = binding.LAYOUT_BLOCKED if layout == "blocked" else binding.LAYOUT_ROWS
+            lay = binding.recommend_layout(P, K, kind, plan)
+            self.arena = torch.empty(max(lay.arena_floats, 1), device=dev, dtype=torch.float32)
+            self.worker_stride = lay.worker_stride
+            self.block_floats, self.block_stride = lay.block_floats, lay.block_stride
+            offs = (0, lay.omega_offset, lay.delta_offset)
+            if layout == "rows":
+                self.width = lay.omega_offset                       # the padded row
+                self.arrays = [torch.as_strided(self.arena, (K, self.width), (lay.worker_stride, 1), o) for o in offs]
+            else:
+                B = lay.block_floats
+                nb = (P + B - 1) // B
+                self.width = nb * B
+                # [K, nb, B] views: element (w, g, r) of array a sits at g*block_stride + a's offset + w*B + r
+                self.arrays = [torch.as_strided(self.arena, (K, nb, B), (lay.worker_stride, lay.block_stride, 1), o)
+                               for o in offs]
+
+    # -- what the library is given --------------------------------------------------------
+    def desc(self, gossip_ma: bool = False):
+        from . import binding
+        t, o, d = self.arrays
+        return binding.make_state(t, None if gossip_ma else o, None if gossip_ma else d, self.worker_stride,
+                                  self.block_floats, self.block_stride)
+
+    @property
+    def bytes(self) -> int:
+        return 4 * (self.arena.numel() if self.arena is not None else sum(a.numel() for a in self.arrays))
+
+    # -- moving values ----------------------------------------------------------------------
+    def view2d(self, which: int) -> torch.Tensor:
+        """[K, width] strided view for rows/separate; for blocked a [K, nb, B] view."""
+        return self.arrays[which]
+
+    def zero_(self):
+        if self.arena is not None:
+            self.arena.zero_()
+        else:
+            for a in self.arrays:
+                a.zero_()
+
+    def set_row(self, which: int, k: int, src: torch.Tensor) -> None:
+        """worker k's first len(src) parameters of array `which` <- src (1-D, device)."""
+        n = src.numel()
+        a = self.arrays[which]
+        if self.layout != "blocked":
+            a[k, :n] = src
+            return
+        B = self.block_floats
+        full = n // B
+        if full:
+            a[k, :full] = src[: full * B].view(full, B)
+        if n % B:
+            a[k, full, : n % B] = src[full * B:]
+
+    def get_row(self, which: int, k: int) -> torch.Tensor:
+        """worker k's P parameters of array `which` as a contiguous 1-D copy."""
+        a = self.arrays[which]
+        if self.layout != "blocked":
+            return a[k, : self.P].clone()
+        return a[k].reshape(-1)[: self.P].clone()
+
+    def add_to_row(self, which: int, k: int, src: torch.Tensor) -> None:
+        self.set_row(which, k, self.get_row(which, k)[: src.numel()] + src)
+
+    def gather(self, which: int, cols: torch.Tensor) -> torch.Tensor:
+        """[K, len(cols)] values of the given element columns (int64 device tensor)."""
+        a = self.arrays[which]
+        if self.layout != "blocked":
+            return a.index_select(1, cols)
+        B = self.block_floats
+        return a[:, cols // B, cols % B]
+
+    def padding(self, which: int) -> torch.Tensor:
+        """The floats of array `which` beyond the P parameters (never touched by the library)."""
+        a = self.arrays[which]
+        if self.layout != "blocked":
+            return a[:, self.P:]
+        B = self.block_floats
+        r = self.P % B
+        return a[:, -1, r:] if r else a[:, :0, 0]
+
+    def to_host(self, which: int):
+        """[K, P] numpy copy."""
+        import numpy as _np
+        if self.layout != "blocked":
+            return self.arrays[which][:, : self.P].cpu().numpy().copy()
+        out = _np.empty((self.K, self.P), dtype=_np.float32)
+        for k in range(self.K):
+            out[k] = self.get_row(which, k).cpu().numpy()
+        return out
 
 
-def default_span_bytes(device, state_bytes: int, want: int = 150 * 10**9) -> Optional[int]:
-    """HBM span for alloc_state: ``want`` if it fits beside 8 GB of head room, else whatever
-    does; None (contiguous layout) if the state itself is larger than that."""
-    free, _ = torch.cuda.mem_get_info(torch.device(device))
-    span = min(want, free - 8 * 10**9)
-    return int(span) if span > state_bytes else None
-
-
-def init_state(w: Workload, device, stride: Optional[int] = None, seed: Optional[int] = None,
-               span_bytes: Optional[int] = None):
-    """theta, omega, delta as [K, P_padded] float32 tensors (or strided views, see alloc_state)
-    on ``device``; the row stride is ``theta.stride(0)``.
-    W0 ~ w0_dist; theta_k = W0 + N(0, drift_std); omega_k = W0; Delta ~ N(0, delta_std) or 0.
-    Padding columns (>= P) are zero.  Generated row by row to bound temporary memory."""
+def init_state(w: Workload, device, layout: str = "blocked", stride: Optional[int] = None, seed: Optional[int] = None,
+               plan=None) -> DeviceState:
+    """Seeded initial state of workload ``w``: W0 ~ w0_dist; theta_k = W0 + N(0, drift_std);
+    omega_k = W0; Delta ~ N(0, delta_std) or 0.  Everything beyond the P parameters is zero.
+    Generated row by row to bound temporary memory; the values do not depend on the layout."""
     P = n_params(w)
     dev = torch.device(device)
-    theta, omega, delta, _ = alloc_state(w.K, P, dev, span_bytes=span_bytes, stride=stride)
+    st = DeviceState(w.K, P, dev, layout, stride=stride, plan=plan)
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed if seed is None else seed)
     if w.w0_dist == "normal":
         w0 = torch.randn(P, generator=g, device=dev, dtype=torch.float32) * w.w0_scale
     else:
         w0 = (torch.rand(P, generator=g, device=dev, dtype=torch.float32) * 2 - 1) * w.w0_scale
-    for t in (theta, omega, delta):
-        t.zero_()
+    st.zero_()
     for k in range(w.K):
-        omega[k, :P] = w0
-        theta[k, :P] = w0 + torch.randn(P, generator=g, device=dev, dtype=torch.float32) * w.drift_std
+        st.set_row(1, k, w0)
+        st.set_row(0, k, w0 + torch.randn(P, generator=g, device=dev, dtype=torch.float32) * w.drift_std)
         if w.delta_std > 0:
-            delta[k, :P] = torch.randn(P, generator=g, device=dev, dtype=torch.float32) * w.delta_std
-    return theta, omega, delta
+            st.set_row(2, k, torch.randn(P, generator=g, device=dev, dtype=torch.float32) * w.delta_std)
+    return st
 
 
-def drift(w: Workload, like: torch.Tensor, P: int, round: int) -> torch.Tensor:
-    """Fresh seeded N(0, drift_std) noise of theta's shape (zero in the padding): the local
-    training steps between two syncs."""
-    g = torch.Generator(device=like.device)
-    g.manual_seed(1_000_003 * (w.seed + 1) + round)
-    out = torch.zeros_like(like)
-    out[:, :P] = torch.randn((like.shape[0], P), generator=g, device=like.device, dtype=torch.float32) * w.drift_std
-    return out
+def drift_row(w: Workload, device, P: int, round: int, k: int) -> torch.Tensor:
+    """Fresh seeded N(0, drift_std) noise for worker k's P parameters: the local training
+    steps between two syncs."""
+    g = torch.Generator(device=torch.device(device))
+    g.manual_seed((1_000_003 * (w.seed + 1) + round) * 1024 + k)
+    return torch.randn(P, generator=g, device=torch.device(device), dtype=torch.float32) * w.drift_std
 
 
 def sample_columns(off: np.ndarray, edge: int = 48, interior: int = 32, seed: int = 0) -> np.ndarray:
@@ -225,3 +305,29 @@ def sample_columns(off: np.ndarray, edge: int = 48, interior: int = 32, seed: in
         cols.append(pick)
         red.append(red[-1] + pick.size)
     return np.concatenate(cols) if cols else np.zeros(0, np.int64), np.asarray(red, dtype=np.int64)
+
+
+def tile_columns(off: np.ndarray, tile_floats: int, seed: int = 0, edge: int = 4) -> Tuple[np.ndarray, np.ndarray]:
+    """Element columns that reach into EVERY tile of a sync: tiles are the stretches of
+    ``tile_floats`` elements between multiples of ``tile_floats`` (counted from the row start),
+    cut at component boundaries.  One seeded element per (tile, component) piece, plus the
+    first and last ``edge`` elements of every component (the 16-byte columns a component edge
+    cuts).  Returns (columns ascending, reduced offsets) like ``sample_columns``."""
+    rng = np.random.default_rng(seed)
+    cols: List[np.ndarray] = []
+    red = [0]
+    for i in range(len(off) - 1):
+        a, b = int(off[i]), int(off[i + 1])
+        if b <= a:
+            red.append(red[-1])
+            continue
+        t0, t1 = a // tile_floats, (b - 1) // tile_floats
+        starts = np.arange(t0, t1 + 1, dtype=np.int64) * tile_floats
+        lo = np.maximum(starts, a)
+        hi = np.minimum(starts + tile_floats, b)
+        pick = lo + (rng.random(lo.size) * (hi - lo)).astype(np.int64)
+        ends = np.concatenate([np.arange(a, min(a + edge, b)), np.arange(max(b - edge, a), b)])
+        pick = np.unique(np.concatenate([pick, ends])).astype(np.int64)
+        cols.append(pick)
+        red.append(red[-1] + pick.size)
+    return (np.concatenate(cols) if cols else np.zeros(0, np.int64)), np.asarray(red, dtype=np.int64)

@@ -26,8 +26,9 @@ def _declared():
 
 def test_library_exports_every_declared_symbol():
     names = _declared()
-    assert {"gbmuf_plan", "gbmuf_sync", "gbmuf_sync_table", "gbmuf_neighbours_host",
-            "gbmuf_neighbours_device", "gbmuf_plan_destroy", "gbmuf_strerror"} <= names
+    assert {"gbmuf_plan", "gbmuf_plan_create", "gbmuf_sync", "gbmuf_sync_state", "gbmuf_sync_table",
+            "gbmuf_sync_step", "gbmuf_final_average", "gbmuf_state_copy", "gbmuf_neighbours_host",
+            "gbmuf_neighbours_device", "gbmuf_plan_destroy", "gbmuf_strerror", "gbmuf_recommend_layout"} <= names
     L = ctypes.CDLL(B.LIB_PATH)
     for n in sorted(names):
         assert hasattr(L, n), n
@@ -95,16 +96,77 @@ def test_bad_plans_are_rejected():
     assert L.gbmuf_plan_info(None, None) == B.GBMUF_EINVAL
 
 
-def test_periods_are_validated_on_the_host():
-    pl = B.Plan([0, 4, 10, 10], K=4, q=1)
-    pl.set_periods([16, 128, 1])
-    pl.set_periods(None)
+def test_periods_and_per_component_q_are_validated_at_plan_creation():
+    off = [0, 4, 10, 10]
+    pl = B.Plan(off, K=4, q=1, periods=[16, 128, 1])
+    assert pl.info.has_periods == 1 and pl.info.mixed_q == 0
+    assert B.Plan(off, K=4, q=1).info.has_periods == 0
     with pytest.raises(B.GbmufError) as e:
-        pl.set_periods([16, 0, 1])
+        B.Plan(off, K=4, q=1, periods=[16, 0, 1])
     assert e.value.code == B.GBMUF_EINVAL
     with pytest.raises(B.GbmufError):
-        pl.set_periods([1, 2])                      # wrong length is caught by the binding
-    assert B.lib().gbmuf_plan_set_periods(None, None) == B.GBMUF_EINVAL
+        B.Plan(off, K=4, q=1, periods=[1, 2])                   # wrong length is caught by the binding
+    pl = B.Plan(off, K=8, q=[0, 4, 2], p=2)
+    assert (pl.info.q, pl.info.mixed_q, pl.info.C) == (4, 1, 4)
+    assert B.Plan(off, K=8, q=[3, 3, 3], p=2).info.mixed_q == 0
+    for bad in ([0, 5, 2], [0, -1, 2]):                          # q_i <= 2p, q_i >= 0
+        with pytest.raises(B.GbmufError) as e:
+            B.Plan(off, K=8, q=bad, p=2)
+        assert e.value.code == B.GBMUF_EINVAL
+
+
+def test_plan_desc_is_checked():
+    L = B.lib()
+    off = np.array([0, 4, 10], dtype=np.int64)
+
+    def desc(**kw):
+        d = B.PlanDesc()
+        d.struct_size = ctypes.sizeof(B.PlanDesc)
+        d.m, d.K, d.q = 2, 4, 1
+        d.comp_offsets = off.ctypes.data
+        for k, v in kw.items():
+            setattr(d, k, v)
+        return d
+
+    h = ctypes.c_void_p()
+    assert L.gbmuf_plan_create(ctypes.byref(h), ctypes.byref(desc())) == B.GBMUF_OK
+    assert L.gbmuf_plan_destroy(h) == B.GBMUF_OK
+    for kw in (dict(struct_size=8), dict(sampling=3), dict(sampling=-1), dict(sweep=2), dict(cache_hints=4),
+               dict(workgroups_per_cu=-1), dict(tile_threads=256), dict(tile_threads=300, tile_slots=2),
+               dict(tile_threads=256, tile_slots=3), dict(comp_offsets=None)):
+        assert L.gbmuf_plan_create(ctypes.byref(h), ctypes.byref(desc(**kw))) == B.GBMUF_EINVAL, kw
+    assert L.gbmuf_plan_create(ctypes.byref(h), None) == B.GBMUF_EINVAL
+    assert L.gbmuf_plan_create(None, ctypes.byref(desc())) == B.GBMUF_EINVAL
+    # a tile shape too small for K workers
+    with pytest.raises(B.GbmufError) as e:
+        B.Plan([0, 64], K=600, q=1, tile=(256, 2))
+    assert e.value.code == B.GBMUF_EINVAL
+    pl = B.Plan([0, 64], K=16, q=1, tile=(512, 2), workgroups_per_cu=3)
+    assert (pl.info.threads, pl.info.tile_columns, pl.info.threads_blocked, pl.info.workgroups_per_cu_blocked) == \
+        (512, 64, 512, 3)
+
+
+def test_ring_degree_beyond_the_ring_is_the_full_ring():
+    # the listing of Definition 1 is complete once p reaches K-1: larger degrees are clamped, and
+    # the candidate order still equals the listing for the degree that was asked for
+    for K, p in [(4, 2**31 - 1), (4, 10_000_000), (5, 3), (5, 4), (5, 100), (1, 7), (2, 9)]:
+        pl = B.Plan([0, 64], K=K, q=0, p=p)
+        assert pl.info.p == min(p, K - 1) and pl.info.C == K - 1
+        for w in range(K):
+            assert pl.candidates_host(w).tolist() == oracle.ring_candidates(w, K, min(p, 4 * K)).tolist()
+
+
+@pytest.mark.parametrize("K,p,q", [(8, 2, [0, 1, 2, 3, 4]), (16, 3, [6, 2, 2, 0, 1, 5]), (4, 1, [1, 2, 0]),
+                                   (64, -1, [63, 1, 7]), (5, 4, [3, 1])])
+def test_host_sampler_with_per_component_q_matches_oracle(K, p, q):
+    m = len(q)
+    off = np.arange(m + 1, dtype=np.int64) * 3
+    for seed in (3, 0xFEEDFACE12345678):
+        pl = B.Plan(off, K, q, p, seed=seed)
+        for rnd in (0, 17, 2**33 + 1):
+            got = pl.neighbours_host(rnd)
+            want = oracle.neighbour_table(m, K, pl.info.p, q, seed, rnd)
+            assert got.shape == want.shape and (got == want).all()
 
 
 def test_paper_shaped_partition_has_16_components():
@@ -113,26 +175,71 @@ def test_paper_shaped_partition_has_16_components():
     assert len(off) - 1 == 16 and off[-1] == W.n_params(w)
     assert len({int(x) for x in (off[1:9] - off[:8])}) == 1       # embedding in 8 even shards (Section 3.2)
     assert W.periods(w).tolist() == [128] * 8 + [16] * 8          # Section 3.3's (16,128)
-    pl = B.Plan(off, w.K, w.q, w.p, seed=0)
+    pl = B.Plan(off, w.K, w.q, w.p, seed=0, periods=W.periods(w))
     assert (pl.info.K, pl.info.p, pl.info.q) == (16, 3, 2)         # Section 3.3, 16 GPUs
 
 
-def test_recommended_layout_interleaves_rows_over_the_requested_span():
+def test_recommended_layouts_are_exactly_the_state():
     P, K = 278626775, 16
-    lay = B.recommend_layout(P, K, 150 * 10**9)
+    rows = B.recommend_layout(P, K, B.LAYOUT_ROWS)
     row = (P + 1023) // 1024 * 1024
-    assert lay.omega_offset == row and lay.delta_offset == 2 * row
-    assert lay.worker_stride % 1024 == 0 and lay.worker_stride >= 3 * row
-    assert lay.arena_floats == (K - 1) * lay.worker_stride + 3 * row
-    assert 0.99 * 150e9 < 4 * lay.arena_floats <= 150e9
-    dense = B.recommend_layout(P, K, 0)
-    assert dense.worker_stride == 3 * row
-    one = B.recommend_layout(10, 1, 10**9)
-    assert one.arena_floats == 3 * 1024
+    assert (rows.omega_offset, rows.delta_offset, rows.worker_stride) == (row, 2 * row, 3 * row)
+    assert rows.block_floats == 0 and rows.arena_floats == 3 * K * row
+    blk = B.recommend_layout(P, K, B.LAYOUT_BLOCKED)
+    Bf = blk.block_floats
+    nb = -(-P // Bf)
+    assert Bf & (Bf - 1) == 0 and blk.worker_stride == Bf and blk.block_stride == 3 * K * Bf
+    assert (blk.omega_offset, blk.delta_offset) == (K * Bf, 2 * K * Bf)
+    assert blk.arena_floats == nb * 3 * K * Bf
+    assert blk.arena_floats <= 1.0001 * 3 * K * P                 # no more memory than the state itself
+    # with a plan the block suits its tile; mismatching K or P is refused
+    pl = B.Plan([0, 1000], K=1, q=0, tile=(256, 16))              # one worker: a tile of 4096 columns
+    assert B.recommend_layout(1000, 1, B.LAYOUT_BLOCKED, pl).block_floats == 4 * 4096
     with pytest.raises(B.GbmufError):
-        B.recommend_layout(-1, 4, 0)
-    with pytest.raises(B.GbmufError):
-        B.recommend_layout(10, 0, 0)
+        B.recommend_layout(999, 1, B.LAYOUT_BLOCKED, pl)
+    for bad in ((-1, 4, 0), (10, 0, 0), (10, 4, 2)):
+        with pytest.raises(B.GbmufError):
+            B.recommend_layout(*bad)
+
+
+def test_state_descriptions_are_checked_on_the_host():
+    # argument errors come before the device check, so these run without a GPU
+    K, P = 4, 1000
+    pl = B.Plan([0, 400, P], K=K, q=1)
+    T4 = 4 * pl.info.tile_columns_blocked
+    base = 1 << 20
+
+    def code(fn, *a):
+        with pytest.raises(B.GbmufError) as e:
+            fn(*a)
+        return e.value.code
+
+    ok_dev = B.GBMUF_EDEVICE if not pl.info.has_device else None
+    rows = B.make_state(base, base + 4 * K * 1024, base + 8 * K * 1024, 1024)
+    bad = [
+        B.make_state(base, base + 4 * K * 1024, base + 8 * K * 1024, P - 1),            # stride < P
+        B.make_state(base, base, base + 8 * K * 1024, 1024),                             # theta == omega
+        B.make_state(base, base + 4 * 1024 + 4 * 999, base + 8 * K * 1024, 1024),       # omega row 0 cuts theta row 1
+        B.make_state(base, base + 4 * K * 1024, base + 4 * K * 1024 + 8, 1024),         # omega/delta shifted by 2 floats
+        B.make_state(None, base, base + 4096, 1024),
+        B.make_state(base, None, base + 4096 * K, 1024),                                 # slots needed in BMUF modes
+        B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4 * 3, 3 * K * T4),   # block not a power of two
+        B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4 // 2, 3 * K * T4),  # block smaller than a tile
+        B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4 // 2, T4, 3 * K * T4),  # rows overlap inside a block group
+        B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4, K * T4 - 1),       # groups overlap
+        B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4, 2 * K * T4),       # delta of group g = theta of g+1
+    ]
+    for st in bad:
+        assert code(pl.sync_state, st, 0.9, 1.0, B.MODE_PAPER, 0) == B.GBMUF_EINVAL
+    good_blocked = B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4, 3 * K * T4)
+    interleaved_rows = B.make_state(base, base + 4096, base + 8192, 3 * 1024)           # [theta_w|omega_w|delta_w]
+    if ok_dev is not None:
+        for st in (rows, good_blocked, interleaved_rows):
+            assert code(pl.sync_state, st, 0.9, 1.0, B.MODE_PAPER, 0) == ok_dev
+        assert code(pl.sync_state, B.make_state(base, None, None, 1024), 0.0, 1.0, B.MODE_GOSSIP_MA, 0) == ok_dev
+    assert code(pl.sync_state, rows, 0.9, 1.0, 7, 0) == B.GBMUF_EINVAL
+    assert code(pl.state_copy, rows, good_blocked, 8) == B.GBMUF_EINVAL
+    assert code(pl.state_copy, B.make_state(base, None, None, 1024), good_blocked, 3) == B.GBMUF_EINVAL
 
 
 def test_bench_refuses_more_than_one_gpu():
@@ -156,14 +263,14 @@ def test_device_calls_need_a_device():
     pl = B.Plan([0, 8], K=4, q=1)
     assert pl.info.has_device == 0
     with pytest.raises(B.GbmufError) as e:
-        pl.sync(16, 32, 48, 8, 0.9, 1.0)
+        pl.sync(4096, 8192, 12288, 8, 0.9, 1.0)
     assert e.value.code == B.GBMUF_EDEVICE
     with pytest.raises(B.GbmufError) as e:
         pl.neighbours_device(0, 16)
     assert e.value.code == B.GBMUF_EDEVICE
     with pytest.raises(B.GbmufError) as e:          # argument errors come first
-        pl.sync(16, 32, 48, 7, 0.9, 1.0)
+        pl.sync(4096, 8192, 12288, 7, 0.9, 1.0)
     assert e.value.code == B.GBMUF_EINVAL
     with pytest.raises(B.GbmufError) as e:
-        pl.sync(16, None, None, 8, 0.9, 1.0, B.MODE_PAPER)
+        pl.sync(4096, None, None, 8, 0.9, 1.0, B.MODE_PAPER)
     assert e.value.code == B.GBMUF_EINVAL
