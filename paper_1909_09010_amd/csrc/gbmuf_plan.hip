@@ -168,14 +168,19 @@ Variant default_variant(int K, int layout)
         const int threads = K <= 32 ? 256 : 1024;
         const int slots = K <= 8 ? 1 : K <= 16 ? 2 : 4;
         find_variant(threads, slots, &v);
-    } else {
-        if (K <= 32) find_variant(512, 1, &v);
-        else find_variant(1024, 4, &v);
+    } else if (K <= 16) {
+        find_variant(512, 1, &v);                          // K = 16: 32 columns (512 B) per worker row
+    } else if (K <= 32) {
+        find_variant(1024, 1, &v);
+    } else if (K <= 64) {
+        find_variant(1024, 2, &v);                         // K = 64: 32 columns again, two slots per thread
     }
     return v;
 }
 
-int32_t default_workgroups_per_cu(int K, int layout) { return layout == kBlocked ? (K <= 32 ? 2 : 2) : 0; }
+// Blocked state: what the chip has in flight should stay near 12 MB (about 24 KB per workgroup
+// at two workgroups per CU, or 96 KB at one); more resident workgroups lose 5-15 points.
+int32_t default_workgroups_per_cu(int K, int layout) { return layout == kBlocked ? (K <= 16 ? 2 : 1) : 0; }
 
 // Split every component into runs of at most T 16-byte columns (the fused kernel's work list).
 void build_tiles(const gbmuf_plan_s &pl, TileSet &ts)
@@ -792,8 +797,9 @@ int gbmuf_recommend_layout(const gbmuf_plan_t *plan, int64_t P, int32_t K, int32
         out->arena_floats = static_cast<int64_t>(K) * 3 * row;
         return GBMUF_OK;
     }
-    // 16 KB blocks measured best (8 KB and 32 KB within a point); a plan with very wide tiles needs more
-    int64_t B = 4096;
+    // 32 KB blocks: K = 16 runs within a point of its best (8-32 KB), K = 64 at its best; 64 KB
+    // blocks lose 7-10 points for both.  A plan with very wide tiles needs more.
+    int64_t B = 8192;
     if (plan)
         while (B < (static_cast<int64_t>(4) << plan->cfg[kBlocked].logT)) B <<= 1;
     const int64_t blocks = (P + B - 1) / B;

@@ -194,7 +194,7 @@ def test_recommended_layouts_are_exactly_the_state():
     assert blk.arena_floats <= 1.0001 * 3 * K * P                 # no more memory than the state itself
     # with a plan the block suits its tile; mismatching K or P is refused
     pl = B.Plan([0, 1000], K=1, q=0, tile=(256, 16))              # one worker: a tile of 4096 columns
-    assert B.recommend_layout(1000, 1, B.LAYOUT_BLOCKED, pl).block_floats == 4 * 4096
+    assert B.recommend_layout(1000, 1, B.LAYOUT_BLOCKED, pl).block_floats == 4 * 4096 > blk.block_floats
     with pytest.raises(B.GbmufError):
         B.recommend_layout(999, 1, B.LAYOUT_BLOCKED, pl)
     for bad in ((-1, 4, 0), (10, 0, 0), (10, 4, 2)):
