@@ -20,8 +20,9 @@
  *   - "host" pointers are ordinary process memory; "device" pointers are HIP device
  *     memory of the GPU that was current when the plan was made.  The caller owns every
  *     buffer it passes; the library copies what it keeps.
- *   - A plan is immutable once made: every call takes it as const, and calls on one plan
- *     may run concurrently from several host threads.
+ *   - A plan is immutable once made: every call takes it as const and none changes it, so
+ *     host threads may share one.  (Device side, syncs of one plan that use its neighbour
+ *     scratch must not be in flight at the same time; see gbmuf_sync.)
  *   - Where the state lives (two layouts, see gbmuf_state_t):
  *       rows     K rows of `worker_stride` floats per array (row w = worker w); the first
  *                P = comp_offsets[m] floats of a row are parameters, the rest is never
@@ -228,6 +229,23 @@ int gbmuf_sync(const gbmuf_plan_t *plan, float *replicas, float *global, float *
                uint64_t round, void *stream);
 int gbmuf_sync_state(const gbmuf_plan_t *plan, const gbmuf_state_t *state, float eta,
                      float zeta, int32_t nesterov, uint64_t round, void *stream);
+
+/*
+ * gbmuf_sync_static -- gbmuf_sync_state for callers that must not allocate or depend on
+ * memory the plan allocated for the sync: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The neighbour table of the sync is drawn (always by the
+ * sampler kernel) into a table that is part of the library's device image -- one array of
+ * GBMUF_STATIC_TABLE_ENTRIES int32 (2 MiB) per GPU, held until the process ends -- instead of
+ * the plan's scratch.  The call makes no allocation of any kind.  Limit: m * K * q (q = the
+ * largest q_i) must not exceed GBMUF_STATIC_TABLE_ENTRIES, else GBMUF_EUNSUPPORTED (nothing
+ * is launched; gbmuf_last_error_detail says how large the table would be).  All plans on one
+ * GPU share that one table: calls of gbmuf_sync_static that are in flight at the same time on
+ * the same GPU race, whichever plans and streams they use.  Results are bit-identical to
+ * gbmuf_sync_state.
+ */
+#define GBMUF_STATIC_TABLE_ENTRIES (1 << 19)
+int gbmuf_sync_static(const gbmuf_plan_t *plan, const gbmuf_state_t *state, float eta,
+                      float zeta, int32_t nesterov, uint64_t round, void *stream);
 
 /*
  * Same update with the neighbours given by the caller: nbr_dev is device memory,

@@ -23,6 +23,7 @@ SAMPLING_AUTO, SAMPLING_IN_KERNEL, SAMPLING_SEPARATE = 0, 1, 2
 SWEEP_AUTO, SWEEP_FORWARD = 0, 1
 LAYOUT_ROWS, LAYOUT_BLOCKED = 0, 1
 MAX_K = 1024
+STATIC_TABLE_ENTRIES = 1 << 19
 
 
 class GbmufError(RuntimeError):
@@ -86,6 +87,8 @@ def _load() -> ctypes.CDLL:
     sp = ctypes.POINTER(State)
     L.gbmuf_sync_state.argtypes = [vp, sp, f32, f32, i32, u64, vp]
     L.gbmuf_sync_step_state.argtypes = [vp, sp, f32, f32, i32, u64, vp]
+    L.gbmuf_sync_static.argtypes = [vp, sp, f32, f32, i32, u64, vp]
+    L.gbmuf_sync_static.restype = ctypes.c_int
     L.gbmuf_sync_table_state.argtypes = [vp, vp, sp, f32, f32, i32, vp]
     L.gbmuf_final_average_state.argtypes = [vp, sp, vp, vp]
     L.gbmuf_state_copy.argtypes = [vp, sp, sp, i32, vp]
@@ -261,6 +264,12 @@ class Plan:
         rc = _lib.gbmuf_sync_state(self._h, ctypes.byref(state), eta, zeta, nesterov, round, _stream(stream))
         if rc != GBMUF_OK:
             raise GbmufError(rc, "gbmuf_sync_state")
+
+    def sync_static(self, state: State, eta: float, zeta: float, nesterov: int = MODE_PAPER, round: int = 0,
+                    stream=None) -> None:
+        rc = _lib.gbmuf_sync_static(self._h, ctypes.byref(state), eta, zeta, nesterov, round, _stream(stream))
+        if rc != GBMUF_OK:
+            raise GbmufError(rc, "gbmuf_sync_static")
 
     def sync_step_state(self, state: State, eta: float, zeta: float, nesterov: int = MODE_PAPER, step: int = 0,
                         stream=None) -> None:

@@ -9,6 +9,7 @@
 #include <cstddef>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -61,6 +62,41 @@ struct gbmuf_plan_s {
     CompDesc *d_comp = nullptr;
     int32_t *d_nbr = nullptr;        // neighbour scratch of gbmuf_sync, [m][K][q]
 };
+
+// ---------------------------------------------------------------------------------------
+// Neighbour table of gbmuf_sync_static: device memory that exists without any allocation call.
+// Every GPU the library runs on holds its own copy of this array (2 MiB) until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the device
+// address is looked up once per device, with that device current, when a plan is made there,
+// and kernels and copies are only ever given that address.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[GBMUF_STATIC_TABLE_ENTRIES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t *g_scratch_ptr[kMaxDevices] = {};
+
+// Looks up this device's copy of `scratch`; `device` must be the current device.
+int resolve_scratch(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return GBMUF_OK;       // gbmuf_sync_static will refuse this device
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device]) return GBMUF_OK;
+    void *p = nullptr;
+    const hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || !p) return gbmuf::hip_failed("hipGetSymbolAddress(scratch)", err, GBMUF_EDEVICE);
+    g_scratch_ptr[device] = static_cast<int32_t *>(p);
+    return GBMUF_OK;
+}
+
+int32_t *scratch_of(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return g_scratch_ptr[device];
+}
+}  // namespace
 
 namespace gbmuf {
 static thread_local char g_detail[256] = "";
@@ -252,6 +288,10 @@ int make_device_state(gbmuf_plan_s &pl, int32_t sampling)
     err = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, pl.device);
     if (err != hipSuccess) return hip_failed("hipDeviceGetAttribute(MaxSharedMemoryPerBlock)", err, GBMUF_EDEVICE);
     pl.lds_per_cu = max_lds;                               // on this GPU one workgroup may take a CU's whole LDS
+    {
+        const int rc0 = resolve_scratch(pl.device);
+        if (rc0 != GBMUF_OK) return rc0;
+    }
     bool can = false;
     int rc = GBMUF_OK;
     for (int l = 0; l < 2 && rc == GBMUF_OK; ++l) {
@@ -647,6 +687,29 @@ int gbmuf_sync_state(const gbmuf_plan_t *plan, const gbmuf_state_t *state, float
     rc = launch_sampler(sample_args(plan, round, plan->d_nbr), s);
     if (rc != GBMUF_OK) return rc;
     return enqueue_sync(plan, plan->d_nbr, state, at, layout, eta, zeta, nesterov, s, round);
+}
+
+int gbmuf_sync_static(const gbmuf_plan_t *plan, const gbmuf_state_t *state, float eta, float zeta, int32_t nesterov,
+                      uint64_t round, void *stream)
+{
+    Placement at{};
+    int layout = kRows;
+    int rc = check_sync(plan, state, nesterov, &at, &layout);
+    if (rc != GBMUF_OK) return rc;
+    const int64_t entries = static_cast<int64_t>(plan->m) * plan->K * plan->q;
+    if (entries > GBMUF_STATIC_TABLE_ENTRIES) {
+        std::snprintf(gbmuf::g_detail, sizeof(gbmuf::g_detail),
+                      "gbmuf_sync_static: the neighbour table has %lld entries, the static table holds %d",
+                      static_cast<long long>(entries), GBMUF_STATIC_TABLE_ENTRIES);
+        return GBMUF_EUNSUPPORTED;
+    }
+    int32_t *table = scratch_of(plan->device);
+    if (!table) return hip_failed("no static table on this device", hipErrorInvalidDevice, GBMUF_EDEVICE);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the sampler fills every row the fused kernel reads, so nothing of an earlier call is seen
+    rc = launch_sampler(sample_args(plan, round, table), s);
+    if (rc != GBMUF_OK) return rc;
+    return enqueue_sync(plan, table, state, at, layout, eta, zeta, nesterov, s, round);
 }
 
 int gbmuf_sync(const gbmuf_plan_t *plan, float *replicas, float *global, float *delta, int64_t worker_stride,
