@@ -10,7 +10,7 @@ launch stream around the very launches that are timed), the same figures for the
 configurations, and the CPU oracle timed on this machine's host cores.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|INDEX] [--layout L]
-                    [--only] [--all] [--no-cpu] [--calibrate]
+                    [--only [--entry-points]] [--all] [--no-cpu] [--calibrate]
 """
 from __future__ import annotations
 
@@ -213,6 +213,8 @@ def main() -> int:
     ap.add_argument("--layout", default="blocked", choices=["blocked", "rows", "separate"],
                     help="state placement: the library's blocked arena (default), its rows arena, or three separate tensors")
     ap.add_argument("--only", action="store_true", help="time the headline workload only (what the profiles run)")
+    ap.add_argument("--entry-points", action="store_true",
+                    help="with --only: still time the gossip-MA branch and the final average on the headline state")
     ap.add_argument("--all", action="store_true", help="also time configs[0], [1] and the paper-shaped (16,128) schedule")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--calibrate", action="store_true",
@@ -233,7 +235,7 @@ def main() -> int:
         return 3
 
     w = workloads.get(args.workload)
-    g = run_gpu(w, args.steps, args.warmup, args.layout, entry_points=not args.only)
+    g = run_gpu(w, args.steps, args.warmup, args.layout, entry_points=args.entry_points or not args.only)
     head = summary(w, g)
     assert head["kernel_ms"] <= head["ms_per_step"] * 1.001, "event-timed launches cannot exceed the wall clock around them"
     algo_bytes = BYTES_PER_WORKER_PARAM * w.K * g["P"]

@@ -139,6 +139,8 @@ typedef struct gbmuf_info {
     int32_t in_kernel_sampling; /* 1 if gbmuf_sync draws the rows inside the fused kernel    */
     int32_t tile_columns_blocked, threads_blocked;   /* the same for blocked state           */
     int32_t workgroups_per_cu_blocked;               /* resident workgroups per CU, blocked  */
+    int32_t tile_columns_blocked_ma;  /* tile width of the gossip-MA branch on blocked state  */
+    int32_t min_block_floats;         /* smallest gbmuf_state_t.block_floats this plan takes  */
 } gbmuf_info_t;
 
 /*
@@ -188,7 +190,7 @@ int gbmuf_neighbours_device(const gbmuf_plan_t *plan, uint64_t round, int32_t *o
  *     X + w * worker_stride + e                                         if block_floats == 0
  *     X + (e / B) * block_stride + w * worker_stride + (e % B)          if block_floats == B > 0
  * rows:     worker_stride >= P.
- * blocked:  B a power of two, at least 4 * tile_columns_blocked and at most 2^30;
+ * blocked:  B a power of two, at least gbmuf_info_t.min_block_floats and at most 2^30;
  *           worker_stride >= B; block_stride >= (K-1) * worker_stride + B.  The last block
  *           of a row may be partly unused; those floats are never touched.
  * theta, omega, delta: device, in/out.  omega and delta may be NULL only with

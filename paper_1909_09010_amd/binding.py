@@ -39,7 +39,8 @@ class Info(ctypes.Structure):
                 ("n_tiles", ctypes.c_int64), ("tile_columns", ctypes.c_int32), ("threads", ctypes.c_int32),
                 ("seed", ctypes.c_uint64), ("mixed_q", ctypes.c_int32), ("has_periods", ctypes.c_int32),
                 ("in_kernel_sampling", ctypes.c_int32), ("tile_columns_blocked", ctypes.c_int32),
-                ("threads_blocked", ctypes.c_int32), ("workgroups_per_cu_blocked", ctypes.c_int32)]
+                ("threads_blocked", ctypes.c_int32), ("workgroups_per_cu_blocked", ctypes.c_int32),
+                ("tile_columns_blocked_ma", ctypes.c_int32), ("min_block_floats", ctypes.c_int32)]
 
 
 class PlanDesc(ctypes.Structure):

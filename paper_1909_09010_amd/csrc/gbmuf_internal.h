@@ -100,7 +100,7 @@ int hip_failed(const char *what, hipError_t err, int status);
 // gbmuf_kernels.hip
 int launch_sampler(const SampleArgs &a, hipStream_t stream);
 int launch_final_average(const float *theta, const Placement &at, int K, int64_t P, float inv, float *out,
-                         hipStream_t stream);
+                         int rows_in_flight, size_t lds_floor, hipStream_t stream);
 int launch_state_copy(float *dst, const Placement &dst_at, const float *src, const Placement &src_at, int K,
                       int64_t P, hipStream_t stream);
 int launch_copy_probe(float *dst, const float *src, int64_t n_floats, int flags, int blocks, hipStream_t stream);

@@ -585,10 +585,13 @@ bool placement_vec4(const Placement &at)
 }
 }  // namespace
 
+// rows_in_flight: 16-byte loads a thread keeps in flight (4, 8 or 16); lds_floor bounds the
+// resident one-wave workgroups per compute unit like in launch_sync.
 int launch_final_average(const float *theta, const Placement &at, int K, int64_t P, float inv, float *out,
-                         hipStream_t stream)
+                         int rows_in_flight, size_t lds_floor, hipStream_t stream)
 {
     if (P <= 0) return GBMUF_OK;
+    if (lds_floor > 60 * 1024) lds_floor = 60 * 1024;      // stays below what needs a raised limit
     const bool vec4 = ((reinterpret_cast<uintptr_t>(theta) | reinterpret_cast<uintptr_t>(out)) & 15u) == 0 &&
                       placement_vec4(at);
     const int64_t threads = vec4 ? (P >> 2) + 1 : P;
@@ -597,9 +600,12 @@ int launch_final_average(const float *theta, const Placement &at, int K, int64_t
     if (blocks > 0x7fffffffLL) return GBMUF_EUNSUPPORTED;
     Placement pl = at;
     void *argv[] = {&theta, &pl, &K, &P, &inv, &out};
-    const void *fn = vec4 ? reinterpret_cast<const void *>(final_average_vec4_kernel<8>)
-                          : reinterpret_cast<const void *>(final_average_vec1_kernel);
-    const hipError_t err = hipLaunchKernel(fn, dim3(static_cast<unsigned>(blocks)), dim3(bs), argv, 0, stream);
+    const void *fn = !vec4 ? reinterpret_cast<const void *>(final_average_vec1_kernel)
+                     : rows_in_flight <= 4 ? reinterpret_cast<const void *>(final_average_vec4_kernel<4>)
+                     : rows_in_flight <= 8 ? reinterpret_cast<const void *>(final_average_vec4_kernel<8>)
+                                           : reinterpret_cast<const void *>(final_average_vec4_kernel<16>);
+    const hipError_t err = hipLaunchKernel(fn, dim3(static_cast<unsigned>(blocks)), dim3(bs), argv,
+                                           vec4 ? lds_floor : 0, stream);
     return err == hipSuccess ? GBMUF_OK : hip_failed("hipLaunchKernel(final average)", err, GBMUF_EDEVICE);
 }
 

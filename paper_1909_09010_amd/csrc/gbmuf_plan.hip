@@ -34,6 +34,8 @@ struct LayoutCfg {
 };
 
 enum { kRows = 0, kBlocked = 1 };
+enum { kBmuf = 0, kMa = 1 };          // the three-array update, or the gossip-MA branch (theta only)
+constexpr int kMaxTileSets = 4;
 
 }  // namespace
 
@@ -47,8 +49,8 @@ struct gbmuf_plan_s {
     std::vector<int32_t> periods;    // m: sync period H_i (all 1 without periods)
     std::vector<int32_t> cand;       // [K][C] ring candidates, order of Definition 1
     std::vector<CompDesc> comp;      // m: per-component constants of the kernels
-    LayoutCfg cfg[2];                // kRows, kBlocked
-    TileSet sets[2];
+    LayoutCfg cfg[2][2];             // [kRows, kBlocked][kBmuf, kMa]
+    TileSet sets[kMaxTileSets];      // one per distinct tile width among the four configurations
     int32_t n_sets = 0;
     float inv = 1.0f;                // 1/(q+1), rounded once (plans with one q)
     int32_t flags = 0;               // load/store cache hints of the fused kernel
@@ -197,26 +199,33 @@ bool find_variant(int threads, int slots, Variant *out)
     return false;
 }
 
-Variant default_variant(int K, int layout)
+Variant default_variant(int K, int layout, int what)
 {
     Variant v{1024, 4};
     if (layout == kRows) {
         const int threads = K <= 32 ? 256 : 1024;
         const int slots = K <= 8 ? 1 : K <= 16 ? 2 : 4;
         find_variant(threads, slots, &v);
-    } else if (K <= 16) {
-        find_variant(512, 1, &v);                          // K = 16: 32 columns (512 B) per worker row
-    } else if (K <= 32) {
-        find_variant(1024, 1, &v);
-    } else if (K <= 64) {
-        find_variant(1024, 2, &v);                         // K = 64: 32 columns again, two slots per thread
+    } else if (what == kBmuf) {
+        if (K <= 16) find_variant(512, 1, &v);             // K = 16: 32 columns (512 B) per worker row
+        else if (K <= 32) find_variant(1024, 1, &v);
+        else if (K <= 64) find_variant(1024, 2, &v);       // K = 64: 32 columns again, two slots per thread
+    } else {
+        if (K <= 16) find_variant(512, 2, &v);             // theta only: twice the columns per workgroup
+        else if (K <= 64) find_variant(1024, 2, &v);
     }
     return v;
 }
 
-// Blocked state: what the chip has in flight should stay near 12 MB (about 24 KB per workgroup
-// at two workgroups per CU, or 96 KB at one); more resident workgroups lose 5-15 points.
-int32_t default_workgroups_per_cu(int K, int layout) { return layout == kBlocked ? (K <= 16 ? 2 : 1) : 0; }
+// Blocked state: what the chip has in flight should stay near 12-16 MB (about 24 KB per
+// workgroup at two workgroups per CU, or 96 KB at one; the gossip-MA branch moves a third of
+// that per workgroup and takes twice as many); more resident workgroups lose 5-15 points.
+int32_t default_workgroups_per_cu(int K, int layout, int what)
+{
+    if (layout != kBlocked) return 0;
+    if (what == kBmuf) return K <= 16 ? 2 : 1;
+    return K <= 16 ? 4 : 2;
+}
 
 // Split every component into runs of at most T 16-byte columns (the fused kernel's work list).
 void build_tiles(const gbmuf_plan_s &pl, TileSet &ts)
@@ -294,9 +303,9 @@ int make_device_state(gbmuf_plan_s &pl, int32_t sampling)
     }
     bool can = false;
     int rc = GBMUF_OK;
-    for (int l = 0; l < 2 && rc == GBMUF_OK; ++l) {
+    for (int l = 0; l < 4 && rc == GBMUF_OK; ++l) {
         bool c = false;
-        rc = prepare_kernels(pl.cfg[l].variant, pl.K, pl.q, pl.C, pl.mixed_q, &c);
+        rc = prepare_kernels(pl.cfg[l / 2][l % 2].variant, pl.K, pl.q, pl.C, pl.mixed_q, &c);
         can = l == 0 ? c : (can && c);
     }
     if (rc != GBMUF_OK) return rc;
@@ -309,7 +318,7 @@ int make_device_state(gbmuf_plan_s &pl, int32_t sampling)
     } else if (sampling == GBMUF_SAMPLING_SEPARATE) {
         pl.in_kernel_sampling = false;
     } else {
-        pl.in_kernel_sampling = can && pl.sets[pl.cfg[kRows].set].tiles.size() <= 8192;
+        pl.in_kernel_sampling = can && pl.sets[pl.cfg[kRows][kBmuf].set].tiles.size() <= 8192;
     }
     if ((rc = upload(&pl.d_cand, pl.cand)) != GBMUF_OK) return rc;
     if ((rc = upload(&pl.d_comp, pl.comp)) != GBMUF_OK) return rc;
@@ -367,6 +376,11 @@ bool arrays_overlap(const float *x, const float *y, int64_t K, int64_t stride, i
     return false;
 }
 
+int32_t max_blocked_logT(const gbmuf_plan_s *pl)
+{
+    return std::max(pl->cfg[kBlocked][kBmuf].logT, pl->cfg[kBlocked][kMa].logT);
+}
+
 // Validates a state description for this plan and turns it into the kernels' placement.
 int check_state(const gbmuf_plan_s *pl, const gbmuf_state_t *st, bool need_slots, Placement *at, int *layout)
 {
@@ -380,7 +394,7 @@ int check_state(const gbmuf_plan_s *pl, const gbmuf_state_t *st, bool need_slots
     } else {
         const int64_t B = st->block_floats;
         if (B < 0 || (B & (B - 1)) != 0 || B > (static_cast<int64_t>(1) << 30)) return GBMUF_EINVAL;
-        if (B < (static_cast<int64_t>(4) << pl->cfg[kBlocked].logT)) return GBMUF_EINVAL;   // a tile must fit a block
+        if (B < (static_cast<int64_t>(4) << max_blocked_logT(pl))) return GBMUF_EINVAL;      // a tile must fit a block
         if (st->worker_stride < B) return GBMUF_EINVAL;
         if (st->block_stride < static_cast<int64_t>(pl->K - 1) * st->worker_stride + B) return GBMUF_EINVAL;
         int32_t lg = 0;
@@ -423,7 +437,7 @@ int enqueue_sync(const gbmuf_plan_s *pl, const int32_t *nbr_dev, const gbmuf_sta
                  int layout, float eta, float zeta, int32_t mode, hipStream_t stream, uint64_t round,
                  TileRange range = TileRange{}, bool check_periods = false)
 {
-    const LayoutCfg &cfg = pl->cfg[layout];
+    const LayoutCfg &cfg = pl->cfg[layout][mode == GBMUF_MODE_GOSSIP_MA ? kMa : kBmuf];
     const TileSet &ts = pl->sets[cfg.set];
     const int64_t n_tiles = range.count < 0 ? static_cast<int64_t>(ts.tiles.size()) : range.count;
     SyncArgs a{};
@@ -545,12 +559,12 @@ int gbmuf_plan_create(gbmuf_plan_t **out, const gbmuf_plan_desc_t *desc)
             }
             pl->flags = desc->cache_hints;
             pl->alternate = desc->sweep == GBMUF_SWEEP_AUTO;
-            for (int l = 0; l < 2 && rc == GBMUF_OK; ++l) {
-                LayoutCfg &cfg = pl->cfg[l];
+            for (int l = 0; l < 4 && rc == GBMUF_OK; ++l) {
+                LayoutCfg &cfg = pl->cfg[l / 2][l % 2];
                 if (desc->tile_threads != 0) {
                     if (!find_variant(desc->tile_threads, desc->tile_slots, &cfg.variant)) rc = GBMUF_EINVAL;
                 } else {
-                    cfg.variant = default_variant(K, l);
+                    cfg.variant = default_variant(K, l / 2, l % 2);
                 }
                 if (rc != GBMUF_OK) break;
                 const int slots = cfg.variant.threads * cfg.variant.slots;
@@ -559,20 +573,21 @@ int gbmuf_plan_create(gbmuf_plan_t **out, const gbmuf_plan_desc_t *desc)
                 while ((static_cast<int64_t>(K) << (lg + 1)) <= slots) ++lg;
                 cfg.logT = lg;                             // T = largest power of two with K*T <= slots
                 cfg.workgroups_per_cu = desc->workgroups_per_cu != 0 ? desc->workgroups_per_cu
-                                                                     : default_workgroups_per_cu(K, l);
+                                                                     : default_workgroups_per_cu(K, l / 2, l % 2);
             }
             if (rc == GBMUF_OK) {
-                pl->sets[0].logT = pl->cfg[kRows].logT;
-                build_tiles(*pl, pl->sets[0]);
-                pl->cfg[kRows].set = 0;
-                pl->n_sets = 1;
-                if (pl->cfg[kBlocked].logT == pl->cfg[kRows].logT) {
-                    pl->cfg[kBlocked].set = 0;
-                } else {
-                    pl->sets[1].logT = pl->cfg[kBlocked].logT;
-                    build_tiles(*pl, pl->sets[1]);
-                    pl->cfg[kBlocked].set = 1;
-                    pl->n_sets = 2;
+                // one tile list per distinct tile width
+                for (int l = 0; l < 4; ++l) {
+                    LayoutCfg &cfg = pl->cfg[l / 2][l % 2];
+                    int found = -1;
+                    for (int s2 = 0; s2 < pl->n_sets; ++s2)
+                        if (pl->sets[s2].logT == cfg.logT) found = s2;
+                    if (found < 0) {
+                        found = pl->n_sets++;
+                        pl->sets[found].logT = cfg.logT;
+                        build_tiles(*pl, pl->sets[found]);
+                    }
+                    cfg.set = found;
                 }
                 rc = make_device_state(*pl, desc->sampling);
             }
@@ -619,16 +634,18 @@ int gbmuf_plan_info(const gbmuf_plan_t *plan, gbmuf_info_t *info)
     info->m = plan->m; info->K = plan->K; info->q = plan->q; info->p = plan->p; info->C = plan->C;
     info->has_device = plan->has_device ? 1 : 0;
     info->P = plan->P;
-    info->n_tiles = static_cast<int64_t>(plan->sets[plan->cfg[kRows].set].tiles.size());
-    info->tile_columns = 1 << plan->cfg[kRows].logT;
-    info->threads = plan->cfg[kRows].variant.threads;
+    info->n_tiles = static_cast<int64_t>(plan->sets[plan->cfg[kRows][kBmuf].set].tiles.size());
+    info->tile_columns = 1 << plan->cfg[kRows][kBmuf].logT;
+    info->threads = plan->cfg[kRows][kBmuf].variant.threads;
     info->seed = plan->seed;
     info->mixed_q = plan->mixed_q ? 1 : 0;
     info->has_periods = plan->has_periods ? 1 : 0;
     info->in_kernel_sampling = plan->in_kernel_sampling ? 1 : 0;
-    info->tile_columns_blocked = 1 << plan->cfg[kBlocked].logT;
-    info->threads_blocked = plan->cfg[kBlocked].variant.threads;
-    info->workgroups_per_cu_blocked = plan->cfg[kBlocked].workgroups_per_cu;
+    info->tile_columns_blocked = 1 << plan->cfg[kBlocked][kBmuf].logT;
+    info->threads_blocked = plan->cfg[kBlocked][kBmuf].variant.threads;
+    info->workgroups_per_cu_blocked = plan->cfg[kBlocked][kBmuf].workgroups_per_cu;
+    info->tile_columns_blocked_ma = 1 << plan->cfg[kBlocked][kMa].logT;
+    info->min_block_floats = 4 << max_blocked_logT(plan);
     return GBMUF_OK;
 }
 
@@ -731,7 +748,7 @@ int gbmuf_sync_step_state(const gbmuf_plan_t *plan, const gbmuf_state_t *state, 
     // The tile list is in component order: the components that are due at this step cover one
     // or more runs of it.  One run is launched as exactly that range; several runs take one
     // launch over everything in which the workgroups of the other components return at once.
-    const TileSet &ts = plan->sets[plan->cfg[layout].set];
+    const TileSet &ts = plan->sets[plan->cfg[layout][nesterov == GBMUF_MODE_GOSSIP_MA ? kMa : kBmuf].set];
     int64_t run_first = 0, run_end = 0;
     int32_t comp_first = -1, comp_last = -1, runs = 0;
     for (int32_t i = 0; i < plan->m; ++i) {
@@ -800,8 +817,18 @@ int gbmuf_final_average_state(const gbmuf_plan_t *plan, const gbmuf_state_t *sta
     int rc = check_state(plan, state, false, &at, &layout);
     if (rc != GBMUF_OK) return rc;
     if ((rc = check_device(plan)) != GBMUF_OK) return rc;
+    // Measured on MI355X: rows: 8 loads per thread, as many one-wave workgroups as fit.  Blocked:
+    // the read stream is one address range, and 32-64 KB in flight per CU is the optimum
+    // (K <= 32: 16 loads x 4 waves; larger K: 4 loads x 8 waves), worth 3-8 points.
+    int rows_in_flight = 8;
+    size_t floor_bytes = 0;
+    if (layout == kBlocked && plan->lds_per_cu > 0) {
+        const int waves = plan->K <= 32 ? 4 : 8;
+        rows_in_flight = plan->K <= 32 ? 16 : 4;
+        floor_bytes = static_cast<size_t>(plan->lds_per_cu / waves - 2048);
+    }
     return launch_final_average(state->theta, at, plan->K, plan->P, 1.0f / static_cast<float>(plan->K), out_dev,
-                                static_cast<hipStream_t>(stream));
+                                rows_in_flight, floor_bytes, static_cast<hipStream_t>(stream));
 }
 
 int gbmuf_final_average(const gbmuf_plan_t *plan, const float *replicas, int64_t worker_stride, float *out_dev,
@@ -864,7 +891,7 @@ int gbmuf_recommend_layout(const gbmuf_plan_t *plan, int64_t P, int32_t K, int32
     // blocks lose 7-10 points for both.  A plan with very wide tiles needs more.
     int64_t B = 8192;
     if (plan)
-        while (B < (static_cast<int64_t>(4) << plan->cfg[kBlocked].logT)) B <<= 1;
+        while (B < (static_cast<int64_t>(4) << max_blocked_logT(plan))) B <<= 1;
     const int64_t blocks = (P + B - 1) / B;
     out->worker_stride = B;
     out->block_floats = B;

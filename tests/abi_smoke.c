@@ -70,7 +70,30 @@ int main(void)
         differ += memcmp(h[a], ref[a], bytes) != 0;
     }
     if (differ) { fprintf(stderr, "%zu of 3 state arrays differ from the oracle\n", differ); return 1; }
+
+    /* The same state moved into the library's blocked arena (gbmuf_recommend_layout,
+     * gbmuf_state_copy), two more syncs there (gbmuf_sync_state), and back to rows. */
+    gbmuf_layout_t lay;
+    CHECK(gbmuf_recommend_layout(plan, P, K, GBMUF_LAYOUT_BLOCKED, &lay));
+    float *arena = NULL;
+    HIP(hipMalloc((void **)&arena, sizeof(float) * (size_t)lay.arena_floats));
+    gbmuf_state_t rows = {d[0], d[1], d[2], stride, 0, 0};
+    gbmuf_state_t blocked = {arena, arena + lay.omega_offset, arena + lay.delta_offset,
+                             lay.worker_stride, lay.block_floats, lay.block_stride};
+    CHECK(gbmuf_state_copy(plan, &blocked, &rows, 7, stream));
+    for (uint64_t round = 3; round < 5; ++round) {
+        CHECK(gbmuf_sync_state(plan, &blocked, eta, zeta, GBMUF_MODE_PAPER, round, stream));
+        CHECK(gbmuf_oracle_sync_f32(off, M, K, info.p, Q, seed, round, NULL, ref[0], ref[1], ref[2], stride, eta, zeta, 1));
+    }
+    CHECK(gbmuf_state_copy(plan, &rows, &blocked, 7, stream));
+    HIP(hipStreamSynchronize(stream));
+    for (int a = 0; a < 3; ++a) {
+        HIP(hipMemcpy(h[a], d[a], bytes, hipMemcpyDeviceToHost));
+        differ += memcmp(h[a], ref[a], bytes) != 0;
+    }
+    if (differ) { fprintf(stderr, "%zu of 3 state arrays differ from the oracle after the blocked syncs\n", differ); return 1; }
     CHECK(gbmuf_plan_destroy(plan));
-    printf("abi_smoke ok: K=%d P=%lld rounds=3, 3 state arrays and 3 neighbour tables bit-identical to the oracle (padding included)\n", K, (long long)P);
+    printf("abi_smoke ok: K=%d P=%lld, 3 syncs in rows and 2 in the blocked arena: 3 state arrays and 3 neighbour tables "
+           "bit-identical to the oracle (padding included)\n", K, (long long)P);
     return 0;
 }

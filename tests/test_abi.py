@@ -204,9 +204,10 @@ def test_recommended_layouts_are_exactly_the_state():
 
 def test_state_descriptions_are_checked_on_the_host():
     # argument errors come before the device check, so these run without a GPU
-    K, P = 4, 1000
+    K, P = 4, 5000
     pl = B.Plan([0, 400, P], K=K, q=1)
-    T4 = 4 * pl.info.tile_columns_blocked
+    T4 = pl.info.min_block_floats
+    assert P > 2 * T4                                      # several block groups
     base = 1 << 20
 
     def code(fn, *a):
@@ -215,14 +216,15 @@ def test_state_descriptions_are_checked_on_the_host():
         return e.value.code
 
     ok_dev = B.GBMUF_EDEVICE if not pl.info.has_device else None
-    rows = B.make_state(base, base + 4 * K * 1024, base + 8 * K * 1024, 1024)
+    R = 8192                                               # a row stride >= P
+    rows = B.make_state(base, base + 4 * K * R, base + 8 * K * R, R)
     bad = [
-        B.make_state(base, base + 4 * K * 1024, base + 8 * K * 1024, P - 1),            # stride < P
-        B.make_state(base, base, base + 8 * K * 1024, 1024),                             # theta == omega
-        B.make_state(base, base + 4 * 1024 + 4 * 999, base + 8 * K * 1024, 1024),       # omega row 0 cuts theta row 1
-        B.make_state(base, base + 4 * K * 1024, base + 4 * K * 1024 + 8, 1024),         # omega/delta shifted by 2 floats
-        B.make_state(None, base, base + 4096, 1024),
-        B.make_state(base, None, base + 4096 * K, 1024),                                 # slots needed in BMUF modes
+        B.make_state(base, base + 4 * K * R, base + 8 * K * R, P - 1),                  # stride < P
+        B.make_state(base, base, base + 8 * K * R, R),                                   # theta == omega
+        B.make_state(base, base + 4 * R + 4 * (P - 1), base + 8 * K * R, R),            # omega row 0 cuts theta row 1
+        B.make_state(base, base + 4 * K * R, base + 4 * K * R + 8, R),                  # omega/delta shifted by 2 floats
+        B.make_state(None, base, base + 4 * K * R, R),
+        B.make_state(base, None, base + 4 * K * R, R),                                   # slots needed in BMUF modes
         B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4 * 3, 3 * K * T4),   # block not a power of two
         B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4 // 2, 3 * K * T4),  # block smaller than a tile
         B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4 // 2, T4, 3 * K * T4),  # rows overlap inside a block group
@@ -232,14 +234,14 @@ def test_state_descriptions_are_checked_on_the_host():
     for st in bad:
         assert code(pl.sync_state, st, 0.9, 1.0, B.MODE_PAPER, 0) == B.GBMUF_EINVAL
     good_blocked = B.make_state(base, base + 4 * T4 * K, base + 8 * T4 * K, T4, T4, 3 * K * T4)
-    interleaved_rows = B.make_state(base, base + 4096, base + 8192, 3 * 1024)           # [theta_w|omega_w|delta_w]
+    interleaved_rows = B.make_state(base, base + 4 * R, base + 8 * R, 3 * R)            # [theta_w|omega_w|delta_w]
     if ok_dev is not None:
         for st in (rows, good_blocked, interleaved_rows):
             assert code(pl.sync_state, st, 0.9, 1.0, B.MODE_PAPER, 0) == ok_dev
-        assert code(pl.sync_state, B.make_state(base, None, None, 1024), 0.0, 1.0, B.MODE_GOSSIP_MA, 0) == ok_dev
+        assert code(pl.sync_state, B.make_state(base, None, None, R), 0.0, 1.0, B.MODE_GOSSIP_MA, 0) == ok_dev
     assert code(pl.sync_state, rows, 0.9, 1.0, 7, 0) == B.GBMUF_EINVAL
     assert code(pl.state_copy, rows, good_blocked, 8) == B.GBMUF_EINVAL
-    assert code(pl.state_copy, B.make_state(base, None, None, 1024), good_blocked, 3) == B.GBMUF_EINVAL
+    assert code(pl.state_copy, B.make_state(base, None, None, R), good_blocked, 3) == B.GBMUF_EINVAL
 
 
 def test_bench_refuses_more_than_one_gpu():

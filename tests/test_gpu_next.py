@@ -146,7 +146,7 @@ def test_final_average_matches_oracle(K, P, pad, shift):
     with pytest.raises(B.GbmufError):
         pl.final_average(theta, P - 1, out)
     # the same values in a blocked placement (smallest legal block, gaps, aligned and not)
-    Bf = 4 * pl.info.tile_columns_blocked
+    Bf = pl.info.min_block_floats
     e = torch.arange(P, device=DEV)
     for ws, gap, sh in ((Bf, 0, 0), (Bf + 4, 8, 0), (Bf, 0, 1)):
         bs = (K - 1) * ws + Bf + gap

@@ -156,7 +156,7 @@ def test_every_neighbour_assignment_on_K4(mode, blocked):
     pl = B.Plan(off, K, q, p, seed=0)
     theta0, omega0, delta0 = _random_state(K, P, stride, seed=mode)
     host0 = _to_host(theta0, omega0, delta0)
-    arena = BlockedArena(K, P, 4 * pl.info.tile_columns_blocked, seed=3) if blocked else None
+    arena = BlockedArena(K, P, pl.info.min_block_floats, seed=3) if blocked else None
     per_worker = [list(itertools.combinations(sorted(oracle.ring_candidates(w, K, p).tolist()), q)) for w in range(K)]
     slots = [per_worker[w] for _ in range(2) for w in range(K)]
     n = 0
@@ -268,7 +268,7 @@ def test_sync_matches_oracle_on_blocked_state(K, p, q, off, pad, shift, rounds, 
     seed = 99 + K
     pl = B.Plan(off, K, q, p, seed=seed)
     mult, extra_ws, gap, base_shift = geo
-    Bf = 4 * pl.info.tile_columns_blocked * mult
+    Bf = pl.info.min_block_floats * mult
     arena = BlockedArena(K, P, Bf, ws=Bf + extra_ws, gap=gap, shift=base_shift, seed=K)
     init = _random_state(K, P, P, seed=K + 11)
     for mode in (1, 3):
@@ -291,7 +291,7 @@ def test_state_copy_moves_between_placements():
     K, P = 8, 70001
     pl = B.Plan([0, 30000, P], K, 2)
     src = _random_state(K, P, P + 3, seed=1)
-    Bf = 4 * pl.info.tile_columns_blocked
+    Bf = pl.info.min_block_floats
     for geo_args in (dict(), dict(ws=Bf + 8, gap=16), dict(shift=1)):
         arena = BlockedArena(K, P, Bf, seed=2, **geo_args)
         rows = B.make_state(*src, P + 3)
@@ -324,7 +324,7 @@ def test_tuning_options_do_not_change_a_bit():
     for opt in options:
         pl = B.Plan(off, K, q, 0, seed=5, **opt)
         rows = [t.clone() for t in init]
-        arena = BlockedArena(K, P, 4 * pl.info.tile_columns_blocked, seed=1)
+        arena = BlockedArena(K, P, pl.info.min_block_floats, seed=1)
         arena.put(init)
         for r in range(3):
             pl.sync(*rows, P, 0.9, 1.0, 1, r, None)
