@@ -207,9 +207,12 @@ Variant default_variant(int K, int layout, int what)
         const int slots = K <= 8 ? 1 : K <= 16 ? 2 : 4;
         find_variant(threads, slots, &v);
     } else if (what == kBmuf) {
-        if (K <= 16) find_variant(512, 1, &v);             // K = 16: 32 columns (512 B) per worker row
-        else if (K <= 32) find_variant(1024, 1, &v);
-        else if (K <= 64) find_variant(1024, 2, &v);       // K = 64: 32 columns again, two slots per thread
+        // 32 columns (512 B) per worker row in workgroups of 512 threads, K/16 slots per thread
+        if (K <= 4) find_variant(256, 1, &v);
+        else if (K <= 16) find_variant(512, 1, &v);
+        else if (K <= 32) find_variant(512, 2, &v);
+        else if (K <= 64) find_variant(512, 4, &v);
+        else if (K <= 128) find_variant(512, 8, &v);
     } else {
         if (K <= 16) find_variant(512, 2, &v);             // theta only: twice the columns per workgroup
         else if (K <= 64) find_variant(1024, 2, &v);
@@ -217,13 +220,13 @@ Variant default_variant(int K, int layout, int what)
     return v;
 }
 
-// Blocked state: what the chip has in flight should stay near 12-16 MB (about 24 KB per
-// workgroup at two workgroups per CU, or 96 KB at one; the gossip-MA branch moves a third of
-// that per workgroup and takes twice as many); more resident workgroups lose 5-15 points.
+// Blocked state: what the chip has in flight should stay near 12-24 MB (24-48 KB per workgroup
+// at two workgroups per CU, or 96 KB at one; the gossip-MA branch moves a third of that per
+// workgroup and takes twice as many); more resident workgroups lose 5-15 points.
 int32_t default_workgroups_per_cu(int K, int layout, int what)
 {
     if (layout != kBlocked) return 0;
-    if (what == kBmuf) return K <= 16 ? 2 : 1;
+    if (what == kBmuf) return K <= 4 ? 4 : K <= 32 ? 2 : 1;
     return K <= 16 ? 4 : 2;
 }
 
