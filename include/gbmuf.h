@@ -194,7 +194,8 @@ int gbmuf_neighbours_device(const gbmuf_plan_t *plan, uint64_t round, int32_t *o
  *           worker_stride >= B; block_stride >= (K-1) * worker_stride + B.  The last block
  *           of a row may be partly unused; those floats are never touched.
  * theta, omega, delta: device, in/out.  omega and delta may be NULL only with
- * GBMUF_MODE_GOSSIP_MA.  The floats the three arrays cover must not overlap (checked: EINVAL).
+ * GBMUF_MODE_GOSSIP_MA.  The floats the three arrays cover (rows: the P parameters of every row;
+ * blocked: every block in full) must not overlap (checked: EINVAL).
  */
 typedef struct gbmuf_state {
     float *theta;            /* the replicas                                   */

@@ -276,3 +276,52 @@ def test_device_calls_need_a_device():
     with pytest.raises(B.GbmufError) as e:
         pl.sync(4096, None, None, 8, 0.9, 1.0, B.MODE_PAPER)
     assert e.value.code == B.GBMUF_EINVAL
+
+
+def test_overlap_check_agrees_with_brute_force_on_random_geometries():
+    # small random row and blocked placements of three arrays inside one arena: the library must
+    # refuse (EINVAL) exactly those in which two arrays share a float (without a GPU an accepted
+    # state ends in EDEVICE: argument errors come first)
+    rng = np.random.default_rng(2024)
+    K = 3
+    plans = {False: (B.Plan([0, 17, 40], K=K, q=1), 40),               # rows: 40 parameters
+             True: (B.Plan([0, 170, 1000], K=K, q=1, tile=(256, 1)), 1000)}   # blocked: 4 block groups
+    if plans[False][0].info.has_device:
+        pytest.skip("uses made-up device addresses: only where no GPU can be reached")
+    base = 1 << 22
+    seen = {True: 0, False: 0}
+
+    def touched(start, ws, Bf, bs, P):
+        # rows: the P parameters of every row; blocked: every block in full (blocks are the unit)
+        cells = set()
+        n = P if not Bf else -(-P // Bf) * Bf
+        for w in range(K):
+            for e in range(n):
+                cells.add(start + w * ws + (e + (e // Bf) * (bs - Bf) if Bf else e))
+        return cells
+
+    for trial in range(300):
+        blocked = trial % 2 == 1
+        plan, P = plans[blocked]
+        if blocked:
+            Bf = int(plan.info.min_block_floats)
+            assert P > 3 * Bf
+            ws = Bf + int(rng.integers(0, 3)) * 4
+            bs = (K - 1) * ws + Bf + int(rng.integers(0, 3)) * (2 * ws)
+        else:
+            Bf, bs = 0, 0
+            ws = P + int(rng.integers(0, 30))
+        span = (K - 1) * ws + (P if not Bf else ((P - 1) // Bf) * bs + Bf)
+        starts = [0, int(rng.integers(0, 2 * span)), int(rng.integers(0, 3 * span))]
+        if trial % 5 == 0:                                         # one behind the other
+            starts = [0, span, 2 * span]
+        if blocked and trial % 5 == 2:                             # omega and delta in the gaps of theta's groups
+            starts = [0, (K - 1) * ws + Bf, (K - 1) * ws + Bf + int(rng.integers(0, 2)) * ws]
+        sets = [touched(s0, ws, Bf, bs, P) for s0 in starts]
+        overlap = bool((sets[0] & sets[1]) or (sets[0] & sets[2]) or (sets[1] & sets[2]))
+        st = B.make_state(base + 4 * starts[0], base + 4 * starts[1], base + 4 * starts[2], ws, Bf, bs)
+        with pytest.raises(B.GbmufError) as e:
+            plan.sync_state(st, 0.9, 1.0, B.MODE_PAPER, 0)
+        assert e.value.code == (B.GBMUF_EINVAL if overlap else B.GBMUF_EDEVICE), (trial, blocked, starts, ws, Bf, bs)
+        seen[overlap] += 1
+    assert seen[True] > 50 and seen[False] > 50
