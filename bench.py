@@ -45,16 +45,15 @@ def measured_traffic(workload: str):
 
 
 def timed_launches(torch, stream, fn, n):
-    """n launches of fn(i), each between two events on the launch stream; mean ms."""
-    pairs = []
+    """n launches of fn(i) with an event on the launch stream before the first, between
+    consecutive ones and after the last; mean ms from one event to the next."""
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    marks[0].record(stream)
     for i in range(n):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
         fn(i)
-        e1.record(stream)
-        pairs.append((e0, e1))
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
-    return sum(a.elapsed_time(b) for a, b in pairs) / max(n, 1)
+    return sum(a.elapsed_time(b) for a, b in zip(marks[:-1], marks[1:])) / max(n, 1)
 
 
 def run_gpu(w, steps: int, warmup: int, layout: str = "blocked", entry_points: bool = False):
@@ -91,8 +90,8 @@ def run_gpu(w, steps: int, warmup: int, layout: str = "blocked", entry_points: b
     for r in range(warmup):
         sync(r)
     torch.cuda.synchronize()
-    # the timed region: `steps` whole syncs back to back; every sync also sits between two events
-    # on the launch stream, which gives the launch durations of the very same syncs
+    # the timed region: `steps` whole syncs back to back, with an event on the launch stream at
+    # every boundary between syncs, which gives the launch durations of the very same syncs
     t0 = time.perf_counter()
     launch_ms = timed_launches(torch, stream, lambda i: sync(warmup + i), steps)
     elapsed = time.perf_counter() - t0
@@ -263,8 +262,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "achieved": head["kernel_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": head["kernel_frac"], "traffic": traffic, "traffic_source": traffic_src,
                      "kernel": "sync_vec4_kernel", "kernel_ms": head["kernel_ms"], "algorithmic_bytes": algo_bytes,
-                     "timing": "mean over the timed syncs, each between two events on the launch stream "
-                               "(the few-microsecond sampler launch of a sync is inside)"},
+                     "timing": "mean over the timed syncs, from events on the launch stream at the boundaries "
+                               "between them (the few-microsecond sampler launch of a sync is inside)"},
     }
     if "entry_points" in g:
         out["other_entry_points"] = g["entry_points"]
