@@ -5,7 +5,9 @@
 // component for ALL K workers, parks the K x T block of theta in LDS (so every worker's
 // average reads its neighbours from LDS, and all reads of theta happen before any write:
 // the in-place update keeps snapshot semantics), and streams omega and Delta through
-// registers; every state byte is read once and written once.
+// registers; every state byte is read once and written once.  Where an element lives is a
+// Placement: plain rows, or blocks of 2^logB floats whose same-index blocks of all workers lie
+// together (one offset per tile, since a tile never crosses a block).
 #include "gbmuf_internal.h"
 
 #include "../../include/gbmuf.h"

@@ -185,8 +185,9 @@ void host_pick(const int32_t *cand, int32_t C, int32_t q, uint64_t seed, uint64_
 // ---------------------------------------------------------------------------------------
 // Measured on MI355X.  Rows (3K address streams): short tiles of about 32 columns (512 B per
 // worker row) with few 16-byte slots per thread, as many workgroups per CU as fit.  Blocked
-// state (one address stream): one slot per thread and only a few workgroups per CU, so that
-// what the whole chip has in flight is a short stretch of memory.
+// state (one address stream): the same 32 columns in workgroups of 512 threads, and only one
+// or two workgroups per CU, so that what the whole chip has in flight is a short stretch of
+// memory.
 bool find_variant(int threads, int slots, Variant *out)
 {
     int count = 0;

@@ -68,3 +68,34 @@ def test_static_table_sync_refuses_a_table_beyond_its_size():
     torch.cuda.synchronize()
     assert torch.equal(st.arena, before)                            # all zeros stay zeros: a fixed point
     pl.destroy()
+
+
+def test_static_table_sync_can_be_captured_in_a_hip_graph_and_replayed():
+    # the call allocates nothing and never synchronises, so it is legal under stream capture; every
+    # replay (with eager work and synchronisation between replays) must equal the eager calls
+    _need_gpu()
+    K, q = 16, 3
+    off = np.concatenate([[0], np.cumsum([5000, 70001, 12, 9000])]).astype(np.int64)
+    P = int(off[-1])
+    pl = B.Plan(off, K, q, 0, seed=9)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(4)
+    graphed = W.DeviceState(K, P, DEV, "blocked", plan=pl)
+    graphed.arena.normal_(0, 0.05, generator=g)
+    eager = W.DeviceState(K, P, DEV, "blocked", plan=pl)
+    eager.arena.copy_(graphed.arena)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for r in range(3):
+            pl.sync_static(graphed.desc(), 0.9, 1.0, B.MODE_PAPER, r, torch.cuda.current_stream())
+    for replay in range(3):
+        graph.replay()
+        for r in range(3):
+            pl.sync_state(eager.desc(), 0.9, 1.0, B.MODE_PAPER, r, None)
+        torch.cuda.synchronize()
+        assert torch.equal(graphed.arena, eager.arena), f"replay {replay}"
+        junk = torch.randn(1 << 20, device=DEV).sum().item()          # eager work between the replays
+        assert junk == junk
+    pl.destroy()
