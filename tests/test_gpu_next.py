@@ -275,3 +275,77 @@ def test_full_size_every_element_invariants_of_one_sync():
     # zeta = 1: omega' equals the average up to the rounding of three additions
     assert float((omega - avg)[:, :P].abs().max()) < 1e-6
     pl.destroy()
+
+
+def test_sync_step_on_blocked_state_with_scattered_periods_and_per_component_q():
+    # the one-launch path (workgroups of components that are not due return at once) and the
+    # one-run path, on the blocked arena, with a different q per component
+    _need_gpu()
+    K = 16
+    sizes = [9000, 300, 70001, 12, 40000, 8192, 1]
+    q = [3, 1, 2, 6, 0, 4, 2]
+    periods = [2, 3, 1, 4, 6, 2, 3]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    P = int(off[-1])
+    for sampling in (B.SAMPLING_SEPARATE, B.SAMPLING_IN_KERNEL):
+        pl = B.Plan(off, K, q, 0, seed=31, periods=periods, sampling=sampling)
+        st = W.DeviceState(K, P, DEV, "blocked", plan=pl)
+        g = torch.Generator(device=DEV)
+        g.manual_seed(8)
+        st.arena.normal_(0, 0.05, generator=g)
+        junk = st.padding(0).clone()
+        host = [st.to_host(a) for a in range(3)]
+        for t in (1, 2, 3, 4, 6, 8, 9, 12):
+            pl.sync_step_state(st.desc(), 0.9, 1.0, B.MODE_PAPER, t, None)
+            oracle.sync(off, K, pl.info.p, q, 31, t, *host, np.float32(0.9), np.float32(1.0), 1,
+                        active=(t % np.asarray(periods) == 0).astype(np.uint8))
+        torch.cuda.synchronize()
+        for a, name in enumerate(("theta", "omega", "delta")):
+            assert (st.to_host(a) == host[a]).all(), (name, sampling)
+        assert torch.equal(st.padding(0), junk)
+        pl.destroy()
+
+
+def test_caller_table_with_per_component_q_ignores_entries_beyond_q_i():
+    _need_gpu()
+    K, q = 8, [1, 3, 0, 2]
+    off = np.array([0, 700, 20000, 20001, 33000], dtype=np.int64)
+    P = int(off[-1])
+    pl = B.Plan(off, K, q, 2, seed=3)
+    nbr = oracle.neighbour_table(4, K, 2, q, seed=3, round=7)
+    junk = nbr.copy()
+    for i, qi in enumerate(q):
+        junk[i, :, qi:] = 12345 + i                            # not worker ids
+    for layout in ("separate", "blocked"):
+        st = W.DeviceState(K, P, DEV, layout, plan=pl)
+        g = torch.Generator(device=DEV)
+        g.manual_seed(2)
+        for buf in ([st.arena] if st.arena is not None else st.arrays):
+            buf.normal_(0, 0.05, generator=g)
+        host = [st.to_host(a) for a in range(3)]
+        table = torch.from_numpy(junk).to(DEV)
+        if layout == "separate":
+            pl.sync_table(table, *st.arrays, st.worker_stride, 0.9, 1.0, B.MODE_PAPER, None)
+        else:
+            pl.sync_table_state(table, st.desc(), 0.9, 1.0, B.MODE_PAPER, None)
+        oracle.sync_table(off, nbr, *host, np.float32(0.9), np.float32(1.0), 1, q=q)
+        torch.cuda.synchronize()
+        for a in range(3):
+            assert (st.to_host(a) == host[a]).all(), (layout, a)
+    pl.destroy()
+
+
+def test_final_average_on_the_rows_arena():
+    _need_gpu()
+    K, P = 16, 300001
+    pl = B.Plan([0, 1000, P], K, 2)
+    st = W.DeviceState(K, P, DEV, "rows", plan=pl)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(6)
+    st.arena.normal_(0, 0.05, generator=g)
+    out = torch.full((P + 3,), -1.0, device=DEV)
+    pl.final_average_state(st.desc(gossip_ma=True), out, None)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert (got[:P] == oracle.final_average(st.to_host(0))).all() and (got[P:] == -1.0).all()
+    pl.destroy()
