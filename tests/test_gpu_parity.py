@@ -657,3 +657,45 @@ def test_config4_k64_every_tile_rows():
 def test_config4b_k64_4layer_every_tile_blocked():
     _need_gpu()
     _run_per_tile(W.get("k64_4layer"), "blocked")
+
+
+@pytest.mark.parametrize("layout", ["blocked", "separate"])
+def test_worker_rows_longer_than_2_to_31_elements(layout):
+    # element offsets beyond 2^31 inside ONE worker row: every index in the kernels is 64-bit.
+    # K = 4 workers of 2^31 + 70,003 parameters (103 GB of state); the oracle replays the rounds on
+    # an element of every 97th tile, the edges of every component and the last 5000 elements.
+    _need_gpu()
+    K, q = 4, 1
+    P = 2**31 + 70003
+    off = np.array([0, 1000, 2**30 + 5, 2**31 - 3, 2**31 + 11, P], dtype=np.int64)
+    pl = B.Plan(off, K, q, 0, seed=12)
+    st = W.DeviceState(K, P, DEV, layout, plan=pl)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(1)
+    for buf in ([st.arena] if st.arena is not None else st.arrays):
+        buf.normal_(0, 0.05, generator=g)
+    T = pl.info.tile_columns_blocked if layout == "blocked" else pl.info.tile_columns
+    cols, _ = W.tile_columns(off, 4 * T * 97, seed=3)
+    cols = np.unique(np.concatenate([cols, np.arange(P - 5000, P, dtype=np.int64)]))
+    red = np.searchsorted(cols, off).astype(np.int64)                # component boundaries among the sampled columns
+    assert cols[-1] == P - 1 and (cols > 2**31).sum() > 5000
+    idx = torch.from_numpy(cols).to(DEV)
+    host = [st.gather(a, idx).cpu().numpy().copy() for a in range(3)]
+    for r in range(3):
+        if layout == "separate":
+            pl.sync(*st.arrays, st.worker_stride, 0.9, 1.0, B.MODE_PAPER, r, None)
+        else:
+            pl.sync_state(st.desc(), 0.9, 1.0, B.MODE_PAPER, r, None)
+        oracle.sync(red, K, pl.info.p, q, 12, r, *host, np.float32(0.9), np.float32(1.0), 1)
+    torch.cuda.synchronize()
+    for a, name in enumerate(("theta", "omega", "delta")):
+        got = st.gather(a, idx).cpu().numpy()
+        assert (got == host[a]).all(), f"{name}: {(got != host[a]).sum()} of {got.size} sampled values differ"
+    out = torch.empty(P, device=DEV)
+    if layout == "separate":
+        pl.final_average(st.arrays[0], st.worker_stride, out, None)
+    else:
+        pl.final_average_state(st.desc(gossip_ma=True), out, None)
+    torch.cuda.synchronize()
+    assert (out.index_select(0, idx).cpu().numpy() == oracle.final_average(np.ascontiguousarray(host[0]))).all()
+    pl.destroy()
