@@ -308,8 +308,9 @@ int gbmuf_final_average_state(const gbmuf_plan_t *plan, const gbmuf_state_t *sta
  *   the kernel streams 3K ranges; measured bandwidth then depends on the physical placement the
  *   allocation happens to get (about 61 % or 73 % of peak for a 53 GB state).
  * EINVAL for P < 0, K < 1, an unknown kind or NULL out; EINVAL too if plan is not NULL and its
- * K or P differ.  With a plan the block size suits that plan's tile shape; with NULL it suits
- * every built-in shape.
+ * K or P differ.  With a plan the block size suits that plan's tile shapes; with NULL it suits
+ * the shapes the library picks by itself for any K (a plan made with very wide tiles may need larger
+ * blocks: gbmuf_info_t.min_block_floats).
  */
 enum { GBMUF_LAYOUT_ROWS = 0, GBMUF_LAYOUT_BLOCKED = 1 };
 typedef struct gbmuf_layout {

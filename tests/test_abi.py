@@ -325,3 +325,12 @@ def test_overlap_check_agrees_with_brute_force_on_random_geometries():
         assert e.value.code == (B.GBMUF_EINVAL if overlap else B.GBMUF_EDEVICE), (trial, blocked, starts, ws, Bf, bs)
         seen[overlap] += 1
     assert seen[True] > 50 and seen[False] > 50
+
+
+def test_the_plan_free_blocked_layout_suits_the_default_shapes_of_every_K():
+    for K in (1, 2, 3, 4, 5, 8, 16, 17, 32, 33, 64, 65, 128, 129, 256, 1000, 1024):
+        pl = B.Plan([0, 100, 5000], K=K, q=0)
+        lay = B.recommend_layout(5000, K, B.LAYOUT_BLOCKED)
+        assert pl.info.min_block_floats <= lay.block_floats, K
+        assert lay.block_floats == B.recommend_layout(5000, K, B.LAYOUT_BLOCKED, pl).block_floats
+        pl.destroy()
